@@ -1,0 +1,182 @@
+/*
+ * slora.h - C ABI of the MI355X heterogeneous batched LoRA library.
+ *
+ * The library adds the low-rank term of the factored LoRA forward pass,
+ *
+ *      y[t,:] += (x[t,:] * A_i) * B_i ,   i = adapter of token t            (Sec. 2, Eq. 2)
+ *
+ * for a batch in which every token names its own adapter and adapters have different ranks
+ * (Sec. 4.1, Fig. 1: the base model's xW is batched by a GEMM, the xAB term by custom kernels
+ * that need no padding).  Adapter weights live in a unified pool that also holds KV-cache
+ * pages: a page is one vector of H elements, a LoRA matrix of rank r occupies r pages placed
+ * anywhere in the pool (Sec. 5.1, Fig. 3).  The decode path (one token per request) is the
+ * paper's gather matrix-vector kernel, the prefill path (a run of tokens per request) its
+ * gather matrix-matrix kernel (Sec. 5.3); here one call serves any mix of both.
+ *
+ * Conventions
+ *   - Every function returns SLORA_OK (0) or a negative error code; nothing throws or aborts.
+ *     slora_last_error() returns a thread-local message for the last failing call.
+ *   - A call validates all of its arguments BEFORE it enqueues device work or changes state:
+ *     after an error the pool, the adapter table and y are as they were.
+ *   - "host" / "device" says where a pointer must point.  Streams are hipStream_t passed as
+ *     void* (NULL = the default stream).  Device work is asynchronous on that stream unless
+ *     a function says otherwise.
+ *   - Storage type of pool pages and of x is IEEE binary16 or bfloat16; y and the
+ *     intermediate v = x*A are fp32; all accumulation is fp32.  No alpha/r scaling is applied
+ *     (Eq. 2 has none): fold any scale into B before upload.
+ *   - Page j of an adapter's A list holds column j of A (an H-vector), page j of its B list
+ *     holds row j of B.  All projections map H -> H.
+ *   - The pool memory is borrowed from the caller and never allocated, freed or cleared here.
+ *     The library allocates (hipMalloc) only its own tables, work lists and the v scratch.
+ *   - A handle must not be used from two threads at once.
+ */
+#ifndef SLORA_H
+#define SLORA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct slora_pool slora_pool; /* page ownership, adapter table, device page lists   */
+typedef struct slora_plan slora_plan; /* one batch's schedule (work lists, v scratch)        */
+
+enum { SLORA_F16 = 0, SLORA_BF16 = 1 };
+
+enum {
+    SLORA_OK = 0,
+    SLORA_EINVAL = -1, /* malformed argument                                              */
+    SLORA_ERANGE = -2, /* page index / slot / rank outside its range                       */
+    SLORA_EBUSY = -3,  /* page already owned, adapter id already loaded, stale plan        */
+    SLORA_ENOENT = -4, /* unknown adapter id                                               */
+    SLORA_ESEG = -5,   /* segment offsets malformed or ids not constant inside a segment   */
+    SLORA_EHIP = -6,   /* a HIP runtime call failed, or the pool has no device memory      */
+    SLORA_ENOMEM = -7
+};
+
+/* Thread-local text for the most recent error returned to this thread ("" if none). */
+const char *slora_last_error(void);
+
+/*
+ * Unified pool (Sec. 5.1).  dev_base: DEVICE pointer to n_pages*page_H 16-bit elements owned
+ * by the caller; page p is elements [p*page_H, (p+1)*page_H).  dev_base may be NULL: the pool
+ * is then host-only - ownership, adapter loading and planning work (for validation and
+ * tests), every call that would touch the device returns SLORA_EHIP.
+ * n_slots = number of (layer, projection) pairs every adapter carries weights for (>= 1).
+ * Requirements: page_H % 8 == 0, 64 <= page_H <= 32768, 1 <= n_pages < 2^31, 0 <= max_rank <= 1024.
+ * The pool uses the HIP device that is current at this call.
+ */
+int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32_t dtype,
+                        void *dev_base, int32_t n_slots, int32_t max_rank);
+
+/* Frees the library's tables.  Plans made from the pool must be destroyed first (EBUSY). */
+int32_t slora_pool_destroy(slora_pool *pool);
+
+/*
+ * Mark pages as holding KV cache (owned != 0) or release them (owned == 0).  page_idx: HOST.
+ * KV pages can never be given to an adapter; the LoRA kernels never read or write them.
+ * Errors: ERANGE (index), EBUSY (page owned by an adapter, or listed twice).
+ */
+int32_t slora_pool_mark_kv(slora_pool *pool, const int32_t *page_idx, int64_t n, int32_t owned);
+
+/*
+ * Copy n H-vectors into the named pages: pool[page_idx[i]] = src[i*H .. (i+1)*H).
+ * page_idx: HOST.  src: HOST if src_on_device == 0, else DEVICE, in the pool's storage type.
+ * Returns after the copy has completed on `stream`.  Ownership is not consulted (the caller
+ * also writes KV pages); only the index range is checked (ERANGE).
+ */
+int32_t slora_pool_write_pages(slora_pool *pool, const int32_t *page_idx, int64_t n,
+                               const void *src, int32_t src_on_device, void *stream);
+
+/*
+ * Make adapter `adapter_id` (any id >= 0) resident with rank `rank`.  page_idx: HOST, n_idx =
+ * n_slots*2*rank entries ordered [slot][A columns j=0..rank-1][B rows j=0..rank-1].  The
+ * pages must already hold (or later receive, before the first apply) the weights.
+ * rank 0 (n_idx 0) is legal: such an adapter contributes exactly nothing.
+ * Errors: EINVAL (id < 0, rank < 0, n_idx mismatch), ERANGE (rank > max_rank, page index),
+ * EBUSY (id already loaded; page KV-owned, owned by another adapter, or repeated).
+ */
+int32_t slora_adapter_load(slora_pool *pool, int32_t adapter_id, int32_t rank,
+                           const int32_t *page_idx, int64_t n_idx);
+
+/* Release the adapter's pages (they become free).  Plans built earlier become stale. */
+int32_t slora_adapter_unload(slora_pool *pool, int32_t adapter_id);
+
+/*
+ * Gather one paged matrix into contiguous DEVICE memory: dev_out[j*H + h] = page j of the A
+ * (which = 0) or B (which = 1) list of (adapter, slot); rank*H elements, bit-exact copies.
+ */
+int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot, int32_t which,
+                             void *dev_out, void *stream);
+
+/*
+ * Schedule a batch (Sec. 4.1: iteration-level batches mix requests of different adapters).
+ * token_adapter_ids[T] and seg_offsets[n_seg+1] are HOST arrays, fully read before return.
+ * A segment is one request's run of consecutive tokens: seg_offsets[0] == 0, strictly
+ * increasing, seg_offsets[n_seg] == T, ids constant inside a segment (else ESEG).
+ * seg_offsets == NULL: every token is its own segment (a pure decode batch); n_seg ignored.
+ * id -1: the token has no adapter and its row of y is never touched.  Unknown id: ENOENT.
+ * The plan groups tokens by adapter, orders groups by rank, routes small groups to the
+ * matrix-vector kernels and large ones to the MFMA kernels, and can be applied to any slot,
+ * any number of times, until an adapter is unloaded.  T == 0 is legal.
+ */
+int32_t slora_batch_plan(slora_pool *pool, slora_plan **out, const int32_t *token_adapter_ids,
+                         int32_t T, const int32_t *seg_offsets, int32_t n_seg);
+int32_t slora_plan_destroy(slora_plan *plan);
+
+/*
+ * Schedule statistics, for tests and tuning: fills out[0..n) (n <= SLORA_PLAN_INFO_N) with
+ *  [0] tokens with an adapter of rank > 0   [1] adapter groups        [2] groups on the vector path
+ *  [3] groups on the MFMA path              [4] vector shrink items   [5] vector expand items
+ *  [6] MFMA shrink items                    [7] MFMA expand items     [8] v row stride (floats)
+ *  [9] sum over groups of rank (pages of A read per slot)
+ */
+#define SLORA_PLAN_INFO_N 10
+int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n);
+
+/*
+ * y[t,:] += (x[t,:] A_i) B_i for every token of the planned batch, weights of `slot`.
+ * x: DEVICE, T*H elements of the pool's storage type, row-major.  y: DEVICE, T*H fp32,
+ * row-major, updated in place.  Asynchronous on `stream`; x and y must stay valid until the
+ * stream has run the work.  Rows of tokens with id -1 or a rank-0 adapter are not accessed.
+ * Results are deterministic: no floating-point atomics, fixed reduction order per plan.
+ */
+int32_t slora_lora_apply(slora_plan *plan, int32_t slot, const void *x, float *y, void *stream);
+
+/*
+ * The same for n slots (1 <= n <= SLORA_MAX_MULTI) in one pair of launches, e.g. the q, k, v
+ * projections of a layer.  slots, x, y: HOST arrays of n entries; x[k] / y[k] are DEVICE
+ * pointers as in slora_lora_apply (entries of x may be equal; entries of y must not overlap).
+ */
+#define SLORA_MAX_MULTI 8
+int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots,
+                               const void *const *x, float *const *y, void *stream);
+
+/*
+ * The two stages on their own (the paper's kernels are a shrink x*A followed by an expand
+ * v*B).  shrink writes v = x*A_i into the plan's scratch; expand adds v*B_i onto y.  An expand
+ * uses the v left by the latest shrink on the same plan with the same n.
+ */
+int32_t slora_lora_shrink(slora_plan *plan, int32_t n, const int32_t *slots,
+                          const void *const *x, void *stream);
+int32_t slora_lora_expand(slora_plan *plan, int32_t n, const int32_t *slots,
+                          float *const *y, void *stream);
+
+/* One-shot form: plan + apply(slot) + plan_destroy; returns after the work has completed. */
+int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
+                                 const int32_t *token_adapter_ids, const int32_t *seg_offsets,
+                                 int32_t n_seg, int32_t T, float *y, void *stream);
+
+/*
+ * Tuning knobs (affect plans made afterwards).  Keys:
+ *   "mfma_min_tokens"  groups with at least this many tokens use the MFMA kernels
+ *                      (default 16; 1 forces everything onto MFMA, a value > 2^30 disables it)
+ * Unknown key: EINVAL.
+ */
+int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLORA_H */

@@ -1,0 +1,373 @@
+// Batch scheduler: turns (adapter id per token, request segments) into device work lists.
+//
+// The paper batches requests of different adapters and ranks in one iteration (Sec. 4.1) and
+// runs the LoRA term with kernels that take no padding (Sec. 5.3); how the work is ordered is
+// left open there.  Here tokens are grouped by adapter so that each adapter's pages are
+// streamed once per group, groups are ordered by rank (longest work first, so the tail of a
+// launch is made of short items), and each group goes either to the wavefront-reduction
+// matrix-vector kernels (few tokens: decode) or to the MFMA kernels (many tokens: prefill).
+// A plan depends only on the ids, so one plan serves every projection of every layer.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "slora_internal.hpp"
+
+using namespace slora;
+
+namespace {
+
+struct Group {
+    int32_t id;
+    int32_t rank;
+    int64_t arena_off;
+    int32_t first_tok;
+    std::vector<int32_t> toks;
+};
+
+int32_t hip_fail(hipError_t e, const char *what) { return fail(SLORA_EHIP, "%s: %s", what, hipGetErrorString(e)); }
+
+} // namespace
+
+int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids, int32_t T,
+                          const int32_t *seg_offsets, int32_t n_seg)
+{
+    // ---- validate ----------------------------------------------------------------------
+    if (T < 0) return fail(SLORA_EINVAL, "T=%d must be >= 0", T);
+    if (T > 0 && !ids) return fail(SLORA_EINVAL, "token_adapter_ids is NULL");
+    if (seg_offsets) {
+        if (n_seg < 0) return fail(SLORA_ESEG, "n_seg=%d must be >= 0", n_seg);
+        if (seg_offsets[0] != 0) return fail(SLORA_ESEG, "seg_offsets[0]=%d must be 0", seg_offsets[0]);
+        if (seg_offsets[n_seg] != T)
+            return fail(SLORA_ESEG, "seg_offsets[n_seg]=%d must equal T=%d", seg_offsets[n_seg], T);
+        for (int32_t s = 0; s < n_seg; ++s) {
+            if (seg_offsets[s + 1] <= seg_offsets[s])
+                return fail(SLORA_ESEG, "seg_offsets must be strictly increasing (segment %d)", s);
+            const int32_t id0 = ids[seg_offsets[s]];
+            for (int32_t t = seg_offsets[s] + 1; t < seg_offsets[s + 1]; ++t)
+                if (ids[t] != id0)
+                    return fail(SLORA_ESEG, "token %d has id %d but its segment %d starts with id %d", t, ids[t], s, id0);
+        }
+    }
+    std::unordered_map<int32_t, int32_t> group_of;
+    std::vector<Group> groups;
+    try {
+        for (int32_t t = 0; t < T; ++t) {
+            const int32_t id = ids[t];
+            if (id == -1) continue;
+            auto g = group_of.find(id);
+            if (g == group_of.end()) {
+                auto a = pool->adapters.find(id);
+                if (id < 0 || a == pool->adapters.end())
+                    return fail(SLORA_ENOENT, "token %d names adapter %d, which is not loaded", t, id);
+                group_of.emplace(id, (int32_t)groups.size());
+                groups.push_back(Group{id, a->second.rank, a->second.arena_off, t, {}});
+                g = group_of.find(id);
+            }
+            groups[(size_t)g->second].toks.push_back(t);
+        }
+
+        // ---- order: rank bucket (descending), then more tokens first, then first appearance --
+        std::vector<int32_t> order;
+        for (int32_t g = 0; g < (int32_t)groups.size(); ++g)
+            if (groups[(size_t)g].rank > 0) order.push_back(g);
+        std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+            const Group &x = groups[(size_t)a], &y = groups[(size_t)b];
+            if (x.rank != y.rank) return x.rank > y.rank;
+            if (x.toks.size() != y.toks.size()) return x.toks.size() > y.toks.size();
+            return x.first_tok < y.first_tok;
+        });
+
+        plan->T = T;
+        plan->tok_idx.clear();
+        plan->vs_items.clear();
+        plan->ve_items.clear();
+        plan->ms_items.clear();
+        plan->me_items.clear();
+        plan->sum_rank = 0;
+        plan->n_groups = (int32_t)order.size();
+        plan->n_groups_vec = plan->n_groups_mfma = 0;
+        plan->max_shrink_tok = 0;
+        int32_t max_rank = 0;
+        const int32_t H = pool->H;
+        for (int32_t gi : order) {
+            const Group &g = groups[(size_t)gi];
+            const int32_t n = (int32_t)g.toks.size();
+            const int32_t pos_base = (int32_t)plan->tok_idx.size();
+            plan->tok_idx.insert(plan->tok_idx.end(), g.toks.begin(), g.toks.end());
+            plan->sum_rank += g.rank;
+            max_rank = std::max(max_rank, g.rank);
+            const int32_t off = (int32_t)g.arena_off;
+            if ((int64_t)n >= pool->mfma_min_tokens) {
+                plan->n_groups_mfma++;
+                for (int32_t p = 0; p < n; p += kMfmaTok) {
+                    const int32_t nt = std::min(kMfmaTok, n - p);
+                    plan->ms_items.push_back(Item{off, g.rank, 0, 0, pos_base + p, nt, 0, 0});
+                    for (int32_t c = 0; c < H; c += kMfmaExpandCols)
+                        plan->me_items.push_back(
+                            Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, 0, 0});
+                }
+            } else {
+                plan->n_groups_vec++;
+                for (int32_t p = 0; p < n; p += kShrinkTok) {
+                    const int32_t nt = std::min(kShrinkTok, n - p);
+                    plan->max_shrink_tok = std::max(plan->max_shrink_tok, nt);
+                    for (int32_t j = 0; j < g.rank; j += kShrinkPages)
+                        plan->vs_items.push_back(
+                            Item{off, g.rank, j, std::min(kShrinkPages, g.rank - j), pos_base + p, nt, 0, 0});
+                }
+                for (int32_t p = 0; p < n; p += kExpandTok) {
+                    const int32_t nt = std::min(kExpandTok, n - p);
+                    for (int32_t c = 0; c < H; c += kExpandCols)
+                        plan->ve_items.push_back(Item{off, g.rank, c, 0, pos_base + p, nt, 0, 0});
+                }
+            }
+        }
+        plan->T_act = (int32_t)plan->tok_idx.size();
+        plan->v_stride = std::max(kRankPad, (max_rank + kRankPad - 1) / kRankPad * kRankPad);
+    } catch (const std::bad_alloc &) {
+        return fail(SLORA_ENOMEM, "out of host memory while planning");
+    }
+    return SLORA_OK;
+}
+
+int32_t slora_plan::upload()
+{
+    if (!pool->dev_base) return SLORA_OK; // host-only pool: the plan stays on the host
+    const size_t n_tok = tok_idx.size();
+    const size_t n_items = vs_items.size() + ve_items.size() + ms_items.size() + me_items.size();
+    if (n_tok == 0) return SLORA_OK;
+    const size_t tok_bytes = (n_tok * sizeof(int32_t) + 31) / 32 * 32;
+    const size_t bytes = tok_bytes + n_items * sizeof(Item);
+    std::vector<unsigned char> img;
+    try {
+        img.resize(bytes);
+    } catch (const std::bad_alloc &) {
+        return fail(SLORA_ENOMEM, "out of host memory while planning");
+    }
+    std::memcpy(img.data(), tok_idx.data(), n_tok * sizeof(int32_t));
+    unsigned char *at = img.data() + tok_bytes;
+    auto put = [&](const std::vector<Item> &v) {
+        if (!v.empty()) std::memcpy(at, v.data(), v.size() * sizeof(Item));
+        at += v.size() * sizeof(Item);
+    };
+    put(vs_items);
+    put(ve_items);
+    put(ms_items);
+    put(me_items);
+    hipError_t e = hipSetDevice(pool->device);
+    if (e == hipSuccess) e = hipMalloc(&d_blob, bytes);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(plan)");
+    e = hipMemcpy(d_blob, img.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(d_blob);
+        d_blob = nullptr;
+        return hip_fail(e, "hipMemcpy(plan)");
+    }
+    d_tok_idx = (int32_t *)d_blob;
+    d_vs = (Item *)((unsigned char *)d_blob + tok_bytes);
+    d_ve = d_vs + vs_items.size();
+    d_ms = d_ve + ve_items.size();
+    d_me = d_ms + ms_items.size();
+    return SLORA_OK;
+}
+
+int32_t slora_plan::ensure_v(int32_t n)
+{
+    const int64_t need = (int64_t)n * T_act * v_stride;
+    if (need <= d_v_cap) return SLORA_OK;
+    hipError_t e = hipSuccess;
+    if (d_v) {
+        e = hipDeviceSynchronize(); // earlier launches may still use the old scratch
+        if (e == hipSuccess) e = hipFree(d_v);
+        d_v = nullptr;
+        d_v_cap = 0;
+    }
+    if (e == hipSuccess) e = hipMalloc((void **)&d_v, (size_t)need * sizeof(float));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(v scratch)");
+    d_v_cap = need;
+    return SLORA_OK;
+}
+
+namespace {
+
+int32_t check_plan(slora_plan *plan, int32_t n, const int32_t *slots)
+{
+    if (!plan) return fail(SLORA_EINVAL, "plan is NULL");
+    if (n < 1 || n > SLORA_MAX_MULTI) return fail(SLORA_EINVAL, "n=%d must be in [1, %d]", n, SLORA_MAX_MULTI);
+    if (!slots) return fail(SLORA_EINVAL, "slots is NULL");
+    for (int32_t k = 0; k < n; ++k)
+        if (slots[k] < 0 || slots[k] >= plan->pool->n_slots)
+            return fail(SLORA_ERANGE, "slot=%d outside [0, %d)", slots[k], plan->pool->n_slots);
+    if (plan->generation != plan->pool->unload_generation)
+        return fail(SLORA_EBUSY, "plan is stale: an adapter was unloaded after it was built");
+    if (!plan->pool->dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
+    return SLORA_OK;
+}
+
+int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *stream)
+{
+    if (!x) return fail(SLORA_EINVAL, "x is NULL");
+    if (plan->T_act == 0) return SLORA_OK;
+    MultiArgs a{};
+    for (int32_t k = 0; k < n; ++k) {
+        if (!x[k]) return fail(SLORA_EINVAL, "x[%d] is NULL", k);
+        if (reinterpret_cast<uintptr_t>(x[k]) & 15) return fail(SLORA_EINVAL, "x[%d] must be 16-byte aligned", k);
+        a.x[k] = x[k];
+        a.slot[k] = slots[k];
+    }
+    int32_t rc = plan->pool->sync_device();
+    if (rc == SLORA_OK) {
+        hipError_t e = hipSetDevice(plan->pool->device);
+        if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
+        rc = plan->ensure_v(n);
+    }
+    if (rc != SLORA_OK) return rc;
+    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->T_act * plan->v_stride;
+    rc = launch_shrink(plan, n, a, stream);
+    if (rc == SLORA_OK) plan->v_slots = n;
+    return rc;
+}
+
+int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *const *y, void *stream)
+{
+    if (!y) return fail(SLORA_EINVAL, "y is NULL");
+    if (plan->T_act == 0) return SLORA_OK;
+    MultiArgs a{};
+    for (int32_t k = 0; k < n; ++k) {
+        if (!y[k]) return fail(SLORA_EINVAL, "y[%d] is NULL", k);
+        if (reinterpret_cast<uintptr_t>(y[k]) & 15) return fail(SLORA_EINVAL, "y[%d] must be 16-byte aligned", k);
+        for (int32_t m = 0; m < k; ++m)
+            if (y[m] == y[k]) return fail(SLORA_EINVAL, "y[%d] and y[%d] are the same buffer", m, k);
+        a.y[k] = y[k];
+        a.slot[k] = slots[k];
+    }
+    if (plan->v_slots != n || !plan->d_v)
+        return fail(SLORA_EINVAL, "expand of %d slot(s) needs a preceding shrink of %d slot(s)", n, n);
+    hipError_t e = hipSetDevice(plan->pool->device);
+    if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
+    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->T_act * plan->v_stride;
+    return launch_expand(plan, n, a, stream);
+}
+
+} // namespace
+
+extern "C" {
+
+int32_t slora_batch_plan(slora_pool *pool, slora_plan **out, const int32_t *token_adapter_ids, int32_t T,
+                         const int32_t *seg_offsets, int32_t n_seg)
+{
+    clear_error();
+    if (!pool || !out) return fail(SLORA_EINVAL, "NULL argument");
+    *out = nullptr;
+    slora_plan *p = new (std::nothrow) slora_plan;
+    if (!p) return fail(SLORA_ENOMEM, "out of host memory");
+    p->pool = pool;
+    p->generation = pool->unload_generation;
+    int32_t rc = build_plan(pool, p, token_adapter_ids, T, seg_offsets, n_seg);
+    if (rc == SLORA_OK) rc = p->upload();
+    if (rc != SLORA_OK) {
+        delete p;
+        return rc;
+    }
+    pool->live_plans++;
+    *out = p;
+    return SLORA_OK;
+}
+
+int32_t slora_plan_destroy(slora_plan *plan)
+{
+    clear_error();
+    if (!plan) return SLORA_OK;
+    if (plan->d_blob || plan->d_v) {
+        (void)hipSetDevice(plan->pool->device);
+        (void)hipDeviceSynchronize();
+        if (plan->d_blob) (void)hipFree(plan->d_blob);
+        if (plan->d_v) (void)hipFree(plan->d_v);
+    }
+    plan->pool->live_plans--;
+    delete plan;
+    return SLORA_OK;
+}
+
+int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n)
+{
+    clear_error();
+    if (!plan || !out || n < 0 || n > SLORA_PLAN_INFO_N) return fail(SLORA_EINVAL, "bad arguments");
+    const int64_t v[SLORA_PLAN_INFO_N] = {plan->T_act,
+                                          plan->n_groups,
+                                          plan->n_groups_vec,
+                                          plan->n_groups_mfma,
+                                          (int64_t)plan->vs_items.size(),
+                                          (int64_t)plan->ve_items.size(),
+                                          (int64_t)plan->ms_items.size(),
+                                          (int64_t)plan->me_items.size(),
+                                          plan->v_stride,
+                                          plan->sum_rank};
+    for (int32_t k = 0; k < n; ++k) out[k] = v[k];
+    return SLORA_OK;
+}
+
+int32_t slora_lora_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *stream)
+{
+    clear_error();
+    int32_t rc = check_plan(plan, n, slots);
+    return rc != SLORA_OK ? rc : do_shrink(plan, n, slots, x, stream);
+}
+
+int32_t slora_lora_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *const *y, void *stream)
+{
+    clear_error();
+    int32_t rc = check_plan(plan, n, slots);
+    return rc != SLORA_OK ? rc : do_expand(plan, n, slots, y, stream);
+}
+
+int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
+                               float *const *y, void *stream)
+{
+    clear_error();
+    int32_t rc = check_plan(plan, n, slots);
+    if (rc != SLORA_OK) return rc;
+    // validate the y side before the shrink is enqueued
+    if (!y) return fail(SLORA_EINVAL, "y is NULL");
+    for (int32_t k = 0; k < n; ++k) {
+        if (!y[k]) return fail(SLORA_EINVAL, "y[%d] is NULL", k);
+        if (reinterpret_cast<uintptr_t>(y[k]) & 15) return fail(SLORA_EINVAL, "y[%d] must be 16-byte aligned", k);
+        for (int32_t m = 0; m < k; ++m)
+            if (y[m] == y[k]) return fail(SLORA_EINVAL, "y[%d] and y[%d] are the same buffer", m, k);
+    }
+    rc = do_shrink(plan, n, slots, x, stream);
+    if (rc != SLORA_OK) return rc;
+    return do_expand(plan, n, slots, y, stream);
+}
+
+int32_t slora_lora_apply(slora_plan *plan, int32_t slot, const void *x, float *y, void *stream)
+{
+    const void *xs[1] = {x};
+    float *ys[1] = {y};
+    return slora_lora_apply_multi(plan, 1, &slot, xs, ys, stream);
+}
+
+int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x, const int32_t *token_adapter_ids,
+                                 const int32_t *seg_offsets, int32_t n_seg, int32_t T, float *y, void *stream)
+{
+    slora_plan *plan = nullptr;
+    int32_t rc = slora_batch_plan(pool, &plan, token_adapter_ids, T, seg_offsets, n_seg);
+    if (rc != SLORA_OK) return rc;
+    rc = slora_lora_apply(plan, slot, x, y, stream);
+    std::string keep = last_error_cstr();
+    if (rc == SLORA_OK) {
+        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "hipStreamSynchronize");
+            keep = last_error_cstr();
+        }
+    }
+    (void)slora_plan_destroy(plan);
+    if (rc != SLORA_OK) fail(rc, "%s", keep.c_str());
+    return rc;
+}
+
+} // extern "C"

@@ -1,0 +1,321 @@
+// Unified pool bookkeeping (Sec. 5.1): page ownership, adapter table, page-list arena and
+// its device image.  Pure host logic plus a few HIP runtime calls; no kernels here.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "slora_internal.hpp"
+
+namespace slora {
+
+static thread_local std::string g_err;
+
+int32_t fail(int32_t code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+void clear_error() { g_err.clear(); }
+const char *last_error_cstr() { return g_err.c_str(); }
+
+static int32_t hip_fail(hipError_t e, const char *what)
+{
+    return fail(SLORA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+} // namespace slora
+
+using namespace slora;
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr); \
+    } while (0)
+
+int32_t slora_pool::sync_device()
+{
+    if (!dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
+    if (dirty_hi <= dirty_lo) return SLORA_OK;
+    HIP_TRY(hipSetDevice(device));
+    const int64_t need = (int64_t)arena.size();
+    if (need > d_arena_cap) {
+        int64_t cap = d_arena_cap ? d_arena_cap : 4096;
+        while (cap < need) cap *= 2;
+        int32_t *fresh = nullptr;
+        HIP_TRY(hipMalloc((void **)&fresh, (size_t)cap * sizeof(int32_t)));
+        if (d_arena) {
+            // kernels that are still running may read the old image
+            hipError_t e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = hipFree(d_arena);
+            if (e != hipSuccess) {
+                (void)hipFree(fresh);
+                return hip_fail(e, "replacing the device page-list arena");
+            }
+        }
+        d_arena = fresh;
+        d_arena_cap = cap;
+        dirty_lo = 0;
+        dirty_hi = need;
+    }
+    HIP_TRY(hipMemcpy(d_arena + dirty_lo, arena.data() + dirty_lo,
+                      (size_t)(dirty_hi - dirty_lo) * sizeof(int32_t), hipMemcpyHostToDevice));
+    dirty_lo = dirty_hi = 0;
+    return SLORA_OK;
+}
+
+extern "C" {
+
+const char *slora_last_error(void) { return last_error_cstr(); }
+
+int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32_t dtype,
+                        void *dev_base, int32_t n_slots, int32_t max_rank)
+{
+    clear_error();
+    if (!out) return fail(SLORA_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (page_H < 64 || page_H > 32768 || page_H % 8)
+        return fail(SLORA_EINVAL, "page_H=%d must be a multiple of 8 in [64, 32768]", page_H);
+    if (n_pages < 1 || n_pages >= (int64_t(1) << 31))
+        return fail(SLORA_EINVAL, "n_pages=%lld must be in [1, 2^31)", (long long)n_pages);
+    if (dtype != SLORA_F16 && dtype != SLORA_BF16) return fail(SLORA_EINVAL, "unknown dtype %d", dtype);
+    if (n_slots < 1 || n_slots > 4096) return fail(SLORA_EINVAL, "n_slots=%d must be in [1, 4096]", n_slots);
+    if (max_rank < 0 || max_rank > 1024) return fail(SLORA_EINVAL, "max_rank=%d must be in [0, 1024]", max_rank);
+    if (dev_base && (reinterpret_cast<uintptr_t>(dev_base) & 15))
+        return fail(SLORA_EINVAL, "dev_base must be 16-byte aligned");
+    int dev = -1;
+    if (dev_base) HIP_TRY(hipGetDevice(&dev));
+    slora_pool *p = new (std::nothrow) slora_pool;
+    if (!p) return fail(SLORA_ENOMEM, "out of host memory");
+    try {
+        p->state.assign((size_t)n_pages, (uint8_t)kFree);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(SLORA_ENOMEM, "out of host memory for %lld page states", (long long)n_pages);
+    }
+    p->H = page_H;
+    p->n_pages = n_pages;
+    p->dtype = dtype;
+    p->dev_base = dev_base;
+    p->n_slots = n_slots;
+    p->max_rank = max_rank;
+    p->device = dev;
+    *out = p;
+    return SLORA_OK;
+}
+
+int32_t slora_pool_destroy(slora_pool *pool)
+{
+    clear_error();
+    if (!pool) return SLORA_OK;
+    if (pool->live_plans) return fail(SLORA_EBUSY, "%lld plan(s) of this pool still exist", (long long)pool->live_plans);
+    if (pool->d_arena) {
+        (void)hipSetDevice(pool->device);
+        (void)hipDeviceSynchronize();
+        (void)hipFree(pool->d_arena);
+    }
+    delete pool;
+    return SLORA_OK;
+}
+
+int32_t slora_pool_mark_kv(slora_pool *pool, const int32_t *page_idx, int64_t n, int32_t owned)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    if (n < 0 || (n > 0 && !page_idx)) return fail(SLORA_EINVAL, "bad page list");
+    // validate, using a temporary mark to detect repeats, then commit
+    const uint8_t kSeen = 0x80;
+    int32_t rc = SLORA_OK;
+    int64_t i = 0;
+    for (; i < n; ++i) {
+        int64_t p = page_idx[i];
+        if (p < 0 || p >= pool->n_pages) {
+            rc = fail(SLORA_ERANGE, "page_idx[%lld]=%lld outside [0, %lld)", (long long)i, (long long)p,
+                      (long long)pool->n_pages);
+            break;
+        }
+        uint8_t s = pool->state[p];
+        if (s & kSeen) {
+            rc = fail(SLORA_EBUSY, "page %lld listed twice", (long long)p);
+            break;
+        }
+        if ((s & 0x7f) == kAdapter) {
+            rc = fail(SLORA_EBUSY, "page %lld is owned by an adapter", (long long)p);
+            break;
+        }
+        pool->state[p] = s | kSeen;
+    }
+    const int64_t marked = i;
+    for (int64_t k = 0; k < marked; ++k) {
+        uint8_t &s = pool->state[page_idx[k]];
+        s = (rc == SLORA_OK) ? (owned ? (uint8_t)kKv : (uint8_t)kFree) : (uint8_t)(s & 0x7f);
+    }
+    return rc;
+}
+
+int32_t slora_pool_write_pages(slora_pool *pool, const int32_t *page_idx, int64_t n, const void *src,
+                               int32_t src_on_device, void *stream)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    if (n < 0 || (n > 0 && (!page_idx || !src))) return fail(SLORA_EINVAL, "bad arguments");
+    for (int64_t i = 0; i < n; ++i)
+        if (page_idx[i] < 0 || page_idx[i] >= pool->n_pages)
+            return fail(SLORA_ERANGE, "page_idx[%lld]=%d outside [0, %lld)", (long long)i, page_idx[i],
+                        (long long)pool->n_pages);
+    if (!pool->dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
+    if (n == 0) return SLORA_OK;
+    HIP_TRY(hipSetDevice(pool->device));
+    hipStream_t st = (hipStream_t)stream;
+    int32_t *d_idx = nullptr;
+    void *d_src = nullptr;
+    int32_t rc = SLORA_OK;
+    hipError_t e = hipMalloc((void **)&d_idx, (size_t)n * sizeof(int32_t));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(page index list)");
+    e = hipMemcpyAsync(d_idx, page_idx, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess && !src_on_device) {
+        const size_t bytes = (size_t)n * pool->H * 2;
+        e = hipMalloc(&d_src, bytes);
+        if (e == hipSuccess) e = hipMemcpyAsync(d_src, src, bytes, hipMemcpyHostToDevice, st);
+    }
+    if (e != hipSuccess) rc = hip_fail(e, "staging pages");
+    if (rc == SLORA_OK) rc = launch_write_pages(pool, d_idx, n, src_on_device ? src : d_src, stream);
+    e = hipStreamSynchronize(st);
+    if (rc == SLORA_OK && e != hipSuccess) rc = hip_fail(e, "hipStreamSynchronize");
+    (void)hipFree(d_idx);
+    if (d_src) (void)hipFree(d_src);
+    return rc;
+}
+
+int32_t slora_adapter_load(slora_pool *pool, int32_t adapter_id, int32_t rank, const int32_t *page_idx,
+                           int64_t n_idx)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    if (adapter_id < 0) return fail(SLORA_EINVAL, "adapter_id=%d must be >= 0", adapter_id);
+    if (rank < 0) return fail(SLORA_EINVAL, "rank=%d must be >= 0", rank);
+    if (rank > pool->max_rank) return fail(SLORA_ERANGE, "rank=%d exceeds max_rank=%d", rank, pool->max_rank);
+    const int64_t want = (int64_t)pool->n_slots * 2 * rank;
+    if (n_idx != want)
+        return fail(SLORA_EINVAL, "n_idx=%lld but n_slots*2*rank=%lld", (long long)n_idx, (long long)want);
+    if (want > 0 && !page_idx) return fail(SLORA_EINVAL, "page_idx is NULL");
+    if (pool->adapters.count(adapter_id)) return fail(SLORA_EBUSY, "adapter %d is already loaded", adapter_id);
+
+    const uint8_t kSeen = 0x80;
+    int32_t rc = SLORA_OK;
+    int64_t i = 0;
+    for (; i < want; ++i) {
+        int64_t p = page_idx[i];
+        if (p < 0 || p >= pool->n_pages) {
+            rc = fail(SLORA_ERANGE, "page_idx[%lld]=%lld outside [0, %lld)", (long long)i, (long long)p,
+                      (long long)pool->n_pages);
+            break;
+        }
+        uint8_t s = pool->state[p];
+        if (s & kSeen) {
+            rc = fail(SLORA_EBUSY, "page %lld appears twice in the list", (long long)p);
+            break;
+        }
+        if (s == kKv) {
+            rc = fail(SLORA_EBUSY, "page %lld holds KV cache", (long long)p);
+            break;
+        }
+        if (s == kAdapter) {
+            rc = fail(SLORA_EBUSY, "page %lld is owned by another adapter", (long long)p);
+            break;
+        }
+        pool->state[p] = s | kSeen;
+    }
+    for (int64_t k = 0; k < i; ++k) pool->state[page_idx[k]] &= 0x7f;
+    if (rc != SLORA_OK) return rc;
+
+    // place the list in the arena (reuse a freed range of the same length if there is one)
+    int64_t off;
+    auto fl = pool->free_lists.find(want);
+    try {
+        if (want > 0 && fl != pool->free_lists.end() && !fl->second.empty()) {
+            off = fl->second.back();
+            fl->second.pop_back();
+        } else {
+            off = (int64_t)pool->arena.size();
+            if (off + want >= (int64_t(1) << 31)) return fail(SLORA_ENOMEM, "page-list arena would exceed 2^31 entries");
+            pool->arena.resize((size_t)(off + want));
+        }
+        pool->adapters.emplace(adapter_id, Adapter{rank, off});
+    } catch (const std::bad_alloc &) {
+        return fail(SLORA_ENOMEM, "out of host memory");
+    }
+    if (want > 0) {
+        std::memcpy(pool->arena.data() + off, page_idx, (size_t)want * sizeof(int32_t));
+        for (int64_t k = 0; k < want; ++k) pool->state[page_idx[k]] = kAdapter;
+        if (pool->dirty_hi <= pool->dirty_lo) {
+            pool->dirty_lo = off;
+            pool->dirty_hi = off + want;
+        } else {
+            if (off < pool->dirty_lo) pool->dirty_lo = off;
+            if (off + want > pool->dirty_hi) pool->dirty_hi = off + want;
+        }
+    }
+    return SLORA_OK;
+}
+
+int32_t slora_adapter_unload(slora_pool *pool, int32_t adapter_id)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    auto it = pool->adapters.find(adapter_id);
+    if (it == pool->adapters.end()) return fail(SLORA_ENOENT, "adapter %d is not loaded", adapter_id);
+    const int64_t len = (int64_t)pool->n_slots * 2 * it->second.rank;
+    const int64_t off = it->second.arena_off;
+    for (int64_t k = 0; k < len; ++k) pool->state[pool->arena[(size_t)(off + k)]] = kFree;
+    if (len > 0) {
+        try {
+            pool->free_lists[len].push_back(off);
+        } catch (const std::bad_alloc &) { /* the range is leaked inside the arena; harmless */
+        }
+    }
+    pool->adapters.erase(it);
+    pool->unload_generation++;
+    return SLORA_OK;
+}
+
+int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot, int32_t which, void *dev_out,
+                             void *stream)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    auto it = pool->adapters.find(adapter_id);
+    if (it == pool->adapters.end()) return fail(SLORA_ENOENT, "adapter %d is not loaded", adapter_id);
+    if (slot < 0 || slot >= pool->n_slots) return fail(SLORA_ERANGE, "slot=%d outside [0, %d)", slot, pool->n_slots);
+    if (which != 0 && which != 1) return fail(SLORA_EINVAL, "which must be 0 (A) or 1 (B)");
+    const int32_t r = it->second.rank;
+    if (r > 0 && !dev_out) return fail(SLORA_EINVAL, "dev_out is NULL");
+    if (r > 0 && (reinterpret_cast<uintptr_t>(dev_out) & 15)) return fail(SLORA_EINVAL, "dev_out must be 16-byte aligned");
+    int32_t rc = pool->sync_device();
+    if (rc != SLORA_OK) return rc;
+    if (r == 0) return SLORA_OK;
+    const int64_t entry = it->second.arena_off + ((int64_t)slot * 2 + which) * r;
+    return launch_gather(pool, entry, r, dev_out, stream);
+}
+
+int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
+{
+    clear_error();
+    if (!pool || !key) return fail(SLORA_EINVAL, "NULL argument");
+    if (!std::strcmp(key, "mfma_min_tokens")) {
+        if (value < 1) return fail(SLORA_EINVAL, "mfma_min_tokens must be >= 1");
+        pool->mfma_min_tokens = value;
+        return SLORA_OK;
+    }
+    return fail(SLORA_EINVAL, "unknown option '%s'", key);
+}
+
+} // extern "C"

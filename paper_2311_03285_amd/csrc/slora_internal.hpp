@@ -1,0 +1,132 @@
+// Internal declarations shared by the host logic (pool, scheduler) and the kernel launchers.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "slora.h"
+
+namespace slora {
+
+// ---------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------
+int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+const char *last_error_cstr();
+
+// ---------------------------------------------------------------------------------------
+// work items (device-visible, 32 bytes)
+// ---------------------------------------------------------------------------------------
+// One record type serves the four work lists; `a` and `b` mean
+//   vector shrink : a = first page j0 of the A list, b = number of pages
+//   vector expand : a = first column (element index),  b = unused
+//   MFMA   shrink : a = unused,                         b = unused
+//   MFMA   expand : a = first column (element index),  b = number of columns
+struct Item {
+    int32_t arena_off; // adapter's first entry in the page-list arena ([slot][A r][B r])
+    int32_t rank;      // r of the adapter
+    int32_t a;
+    int32_t b;
+    int32_t pos0;      // first position in the sorted token list (also the row of v)
+    int32_t ntok;      // tokens handled by this item
+    int32_t pad0;
+    int32_t pad1;
+};
+static_assert(sizeof(Item) == 32, "Item must stay 32 bytes");
+
+// Per-launch arguments for up to SLORA_MAX_MULTI slots handled by one grid (blockIdx.y).
+struct MultiArgs {
+    const void *x[SLORA_MAX_MULTI];
+    float *y[SLORA_MAX_MULTI];
+    float *v[SLORA_MAX_MULTI];
+    int32_t slot[SLORA_MAX_MULTI];
+};
+
+// Tile constants the scheduler and the kernels must agree on.
+constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows staged in LDS)
+constexpr int kShrinkPages = 8;   // pages per vector-shrink item
+constexpr int kExpandTok = 8;     // tokens per vector-expand item (accumulators in registers)
+constexpr int kExpandCols = 512;  // columns per vector-expand item (one wavefront x 8 elements)
+constexpr int kMfmaTok = 32;      // tokens per MFMA item (one 32-row MFMA block)
+constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item
+constexpr int kRankPad = 32;      // v rows are zero-padded to a multiple of this many ranks
+
+// ---------------------------------------------------------------------------------------
+// pool
+// ---------------------------------------------------------------------------------------
+enum PageState : uint8_t { kFree = 0, kKv = 1, kAdapter = 2 };
+
+struct Adapter {
+    int32_t rank;
+    int64_t arena_off; // into the arena, n_slots*2*rank entries
+};
+
+} // namespace slora
+
+struct slora_pool {
+    int32_t H = 0;
+    int64_t n_pages = 0;
+    int32_t dtype = 0;
+    void *dev_base = nullptr;
+    int32_t n_slots = 0;
+    int32_t max_rank = 0;
+    int device = -1;
+
+    std::vector<uint8_t> state;                       // per page
+    std::unordered_map<int32_t, slora::Adapter> adapters;
+    std::vector<int32_t> arena;                       // host image of all page lists
+    std::unordered_map<int64_t, std::vector<int64_t>> free_lists; // length -> offsets
+    int32_t *d_arena = nullptr;                       // device image
+    int64_t d_arena_cap = 0;                          // entries
+    int64_t dirty_lo = 0, dirty_hi = 0;               // [lo, hi) not yet on the device
+    uint64_t unload_generation = 0;
+    int64_t live_plans = 0;
+    int64_t mfma_min_tokens = 16;
+
+    int32_t sync_device();                            // push dirty arena range
+};
+
+struct slora_plan {
+    slora_pool *pool = nullptr;
+    uint64_t generation = 0;
+    int32_t T = 0;        // tokens in the batch
+    int32_t T_act = 0;    // tokens that have an adapter of rank > 0
+    int32_t v_stride = 0; // floats per row of v
+    int32_t max_shrink_tok = 0;
+    int64_t sum_rank = 0;
+    int32_t n_groups = 0, n_groups_vec = 0, n_groups_mfma = 0;
+
+    // host image
+    std::vector<int32_t> tok_idx;                     // sorted position -> token index
+    std::vector<slora::Item> vs_items, ve_items, ms_items, me_items;
+
+    // device image (one allocation)
+    void *d_blob = nullptr;
+    int32_t *d_tok_idx = nullptr;
+    slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_ms = nullptr, *d_me = nullptr;
+
+    float *d_v = nullptr; // scratch for v = x*A, n * T_act * v_stride floats
+    int64_t d_v_cap = 0;
+    int32_t v_slots = 0;  // n of the latest shrink
+
+    int32_t upload();
+    int32_t ensure_v(int32_t n);
+};
+
+namespace slora {
+
+// scheduler (plan.cpp)
+int32_t build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids, int32_t T,
+                   const int32_t *seg_offsets, int32_t n_seg);
+
+// kernel launchers (kernels.hip); all return a SLORA_* code
+int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, const void *d_src,
+                           void *stream);
+int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void *dev_out, void *stream);
+int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
+
+} // namespace slora
