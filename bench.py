@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched-LoRA hot path on one MI355X.
+
+A step = one pass of the whole path (plan already built: shrink + expand for every projection
+slot of the workload) over one batch of synthetic input that is resident in HBM.  Steps rotate
+over several distinct batches drawn against the same resident adapters, so consecutive steps
+do not find their pages in the caches.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 4] [--law power|zipf]
+                    [--batches R] [--mode fused|qkv_o|per_slot] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--law", default="power", choices=["power", "zipf"])
+    ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
+    ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2311_03285_amd import slora, synth
+    from paper_2311_03285_amd.harness import DeviceWorkload, bits_to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    slora.lib()                                   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t_setup = time.time()
+    R = max(1, args.batches)
+    wls = [synth.config(args.workload, batch=b, law=args.law) for b in range(R)]
+    w0 = wls[0]
+    n_slots = w0.n_slots
+    # the pool: every adapter loaded at its scattered pages; seeded weights for the adapters of
+    # batch 0 (the oracle's sample uses them), finite filler for the rest, NaN on KV pages
+    dw = DeviceWorkload(w0, device=dev, real_adapters="used", slots=list(range(min(n_slots, 4))))
+    log(f"[bench] pool ready: {w0.name}, {w0.n_pages} pages x {w0.H} ({w0.n_pages * w0.H * 2 / 1e9:.1f} GB), "
+        f"{w0.n_adapters} adapters, {n_slots} slots, setup {time.time() - t_setup:.1f}s")
+
+    stream = torch.cuda.Stream(device=dev)
+    plans, xs, ys = [], [], []
+    for b, w in enumerate(wls):
+        plans.append(dw.plan(ids=w.ids, seg_offsets=w.seg_offsets))
+        # two activation buffers per batch (attention input for q/k/v, attention output for o),
+        # one y per slot
+        xa = bits_to_device(w.x_bits(0), dev)
+        xb = bits_to_device(w.x_bits(3 if n_slots > 3 else 0), dev)
+        xs.append((xa, xb))
+        ys.append([torch.from_numpy(w.y_in(s % 4)).to(dev) for s in range(n_slots)])
+    torch.cuda.synchronize()
+    info = slora.plan_info(plans[0])
+    log(f"[bench] plan[0]: {info}")
+
+    slots = list(range(n_slots))
+
+    def x_of(b, s):
+        return xs[b][1 if (s % 4) == 3 else 0].data_ptr()
+
+    def step(b):
+        p = plans[b]
+        if args.mode == "fused":
+            for g0 in range(0, n_slots, slora.MAX_MULTI):
+                g = slots[g0:g0 + slora.MAX_MULTI]
+                slora.lora_apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
+        elif args.mode == "qkv_o":
+            for l0 in range(0, n_slots, 4):
+                g = slots[l0:l0 + 3]
+                slora.lora_apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
+                for s in slots[l0 + 3:l0 + 4]:
+                    slora.lora_apply(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
+        else:
+            for s in slots:
+                slora.lora_apply(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
+
+    # ---- timed region: K steps, inputs resident -------------------------------------------
+    for i in range(args.warmup):
+        step(i % R)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(args.steps):
+        step(i % R)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = e0.elapsed_time(e1)
+    ms_per_step = wall * 1e3 / args.steps
+    tok_per_step = float(np.mean([w.T for w in wls]))
+    bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
+    flops_step = float(np.mean([w.flops() for w in wls])) * n_slots
+    value = tok_per_step * args.steps / wall
+
+    # ---- per-kernel durations (HIP events on the launch stream), stage by stage ---------------
+    def stage_times(n_rep):
+        sh, ex = [], []
+        for i in range(n_rep):
+            b = i % R
+            p = plans[b]
+            for g0 in range(0, n_slots, slora.MAX_MULTI):
+                g = slots[g0:g0 + slora.MAX_MULTI]
+                ea, eb, ec = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                ea.record(stream)
+                slora.lora_shrink(p, g, [x_of(b, s) for s in g], stream)
+                eb.record(stream)
+                slora.lora_expand(p, g, [ys[b][s].data_ptr() for s in g], stream)
+                ec.record(stream)
+                sh.append((ea, eb, len(g), b))
+                ex.append((eb, ec, len(g), b))
+        torch.cuda.synchronize()
+        f = lambda L: [(a.elapsed_time(b_) * 1e-3, n, b) for a, b_, n, b in L]
+        return f(sh), f(ex)
+
+    stage_times(min(args.warmup, 8))
+    sh, ex = stage_times(max(8, min(args.steps, 64)))
+    sh_bytes = {b: wls[b].shrink_bytes() for b in range(R)}
+    ex_bytes = {b: wls[b].expand_bytes() for b in range(R)}
+    sh_t = float(np.mean([t for t, n, b in sh]))
+    ex_t = float(np.mean([t for t, n, b in ex]))
+    sh_gbs = float(np.mean([sh_bytes[b] * n / t for t, n, b in sh])) / 1e9
+    ex_gbs = float(np.mean([ex_bytes[b] * n / t for t, n, b in ex])) / 1e9
+    dom = "expand" if ex_t >= sh_t else "shrink"
+    dom_gbs = ex_gbs if dom == "expand" else sh_gbs
+    kinds = ("mfma" if info["groups_mfma"] and not info["groups_vec"] else
+             "vec" if not info["groups_mfma"] else "vec+mfma")
+    roofline = {
+        "bound": "hbm", "kernel": f"{dom}_{kinds}", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+        "avg_launch_us": round((ex_t if dom == "expand" else sh_t) * 1e6, 2),
+        "other_kernel": {"kernel": f"{'shrink' if dom == 'expand' else 'expand'}_{kinds}",
+                         "achieved": round(sh_gbs if dom == "expand" else ex_gbs, 1),
+                         "avg_launch_us": round((sh_t if dom == "expand" else ex_t) * 1e6, 2)},
+        "slots_per_launch": min(n_slots, slora.MAX_MULTI),
+    }
+
+    # ---- check the timed path against the oracle on a sample, and time the oracle ----------
+    cpu = None
+    if not args.no_cpu:
+        from oracle import c_oracle
+        w = w0
+        x0 = w.x_bits(0)
+        y0 = w.y_in(0)
+        rows, lists = w.compact_pool(0)
+        # calibrate on a few tokens, then size the sample to ~cpu_seconds
+        n_cal = min(w.T, 8)
+        tc = time.perf_counter()
+        c_oracle.lora_apply(rows, w.dtype, lists, w.ids[:n_cal], x0[:n_cal], y0[:n_cal])
+        per_tok = (time.perf_counter() - tc) / n_cal
+        n_s = int(max(n_cal, min(w.T, args.cpu_seconds / max(per_tok, 1e-9))))
+        tc = time.perf_counter()
+        ref, cores = c_oracle.lora_apply(rows, w.dtype, lists, w.ids[:n_s], x0[:n_s], y0[:n_s],
+                                         return_threads=True)
+        dt = time.perf_counter() - tc
+        # same sample through the GPU path (fresh y)
+        xg = bits_to_device(x0, dev)
+        yg = torch.from_numpy(y0).to(dev)
+        slora.lora_apply(plans[0], 0, xg.data_ptr(), yg.data_ptr(), stream)
+        torch.cuda.synchronize()
+        got = yg[:n_s].cpu().numpy().astype(np.float64)
+        rel = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        mx = float(np.abs(got - ref).max())
+        if not (rel <= 1e-3 and mx <= 1e-2):
+            print(f"bench.py: GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})",
+                  file=sys.stderr)
+            return 1
+        cpu = {"value": round(n_s / (dt * n_slots), 2), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {n_s} of {w.T} tokens of batch 0, slot 0 timed ({dt:.2f}s) and scaled to "
+                         f"{n_slots} slots per token",
+               "gpu_vs_oracle_rel_l2": rel, "gpu_vs_oracle_max_abs": mx}
+
+    out = {
+        "metric": "lora_tokens_per_s", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w0.name, "H": w0.H, "storage": "fp16" if w0.dtype == 0 else "bf16",
+                   "adapters": w0.n_adapters, "tokens_per_step": tok_per_step, "slots": n_slots,
+                   "pool_pages": w0.n_pages, "popularity": args.law, "rotating_batches": R,
+                   "launch_mode": args.mode,
+                   "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
+        "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
+        "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "mfma_util": round(flops_step / (wall / args.steps) / 1e12 / MFMA_PEAK_TFLOPS, 5),
+        "algorithmic_bytes_per_step": int(bytes_step), "flops_per_step": int(flops_step),
+        "event_ms_per_step": round(ev_ms / args.steps, 5),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    dw.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

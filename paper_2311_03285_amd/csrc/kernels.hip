@@ -238,6 +238,287 @@ __global__ __launch_bounds__(kWave) void expand_vec_kernel(const Item *__restric
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// prefill path (MFMA).  Matrix blocks are 32 x 32 with 16 k-values per instruction
+// (v_mfma_f32_32x32x16_{f16,bf16}): lane l supplies, for row/column l % 32, the 8 k-values
+// 8*(l / 32) .. +7 of both operands, and receives D[8*(v/4) + 4*(l/32) + v%4][l % 32] in
+// accumulator register v (0..15).
+// ---------------------------------------------------------------------------------------
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+__device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f32x16 &c)
+{
+    if constexpr (DT == SLORA_F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0,
+                                                      0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
+                                                       0, 0, 0);
+}
+
+// accumulator register v of lane `lane` holds this row of the 32 x 32 block
+__device__ __forceinline__ int mfma_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// ---------------------------------------------------------------------------------------
+// prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for a tile of up to 32 tokens of
+// one adapter and up to 128 of its ranks.
+//
+// The four wavefronts of a workgroup split H: wavefront w takes the 64-element slices
+// 64*(4c + w).  Inside a slice, lane (row, q = l/32) owns 64 contiguous bytes of its row
+// (x row for the first operand, A page for the second) and feeds them to four MFMAs 16 bytes
+// at a time; both operands use the same assignment of k-values, which is all the instruction
+// needs.  Operands go from global memory straight to registers: every 128-byte line of x and
+// of the pages is fetched by exactly two lanes of one load group.  The four partial tiles are
+// summed through LDS in a fixed order and written once (no atomics).  Ranks beyond the
+// adapter's own, up to the next multiple of 32, are written as zeros so that the expand can
+// read whole blocks.
+// ---------------------------------------------------------------------------------------
+constexpr int kMfmaThreads = 256;
+
+template <int DT>
+__global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *__restrict__ items,
+                                                                    const int32_t *__restrict__ arena,
+                                                                    const uint16_t *__restrict__ pool,
+                                                                    const int32_t *__restrict__ tok_idx, int H,
+                                                                    int v_stride, MultiArgs args)
+{
+    __shared__ float red[4][16][kWave];
+    const Item it = items[blockIdx.x];
+    const int cs = blockIdx.y;
+    const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
+    float *__restrict__ v = args.v[cs];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int row = lane & 31;
+    const int q = lane >> 5;
+    const int j0 = it.a, nj = it.b;
+    const int nblk = (nj + 31) >> 5; // 1..4 blocks of 32 ranks
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + j0;
+
+    const bool x_ok = row < it.ntok;
+    const uint16_t *xrow = x + (x_ok ? (int64_t)tok_idx[it.pos0 + row] * H : 0);
+    bool p_ok[4];
+    const uint16_t *prow[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        const int j = nb * 32 + row;
+        p_ok[nb] = j < nj;
+        prow[nb] = pool + (p_ok[nb] ? (int64_t)pa[j] * H : 0);
+    }
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    for (int h0 = wave * 64; h0 < H; h0 += 4 * 64) {
+        const int hl = h0 + 32 * q;
+        u32x4 xa[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int h = hl + 8 * s;
+            xa[s] = (x_ok && h < H) ? *reinterpret_cast<const u32x4 *>(xrow + h) : zero;
+        }
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            if (nb < nblk) {
+                u32x4 pb[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int h = hl + 8 * s;
+                    pb[s] = (p_ok[nb] && h < H) ? *reinterpret_cast<const u32x4 *>(prow[nb] + h) : zero;
+                }
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc[nb] = mfma32<DT>(xa[s], pb[s], acc[nb]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        if (nb < nblk) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[nb][e];
+            __syncthreads();
+            for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
+                const int vv = e >> 6, l = e & 63;
+                const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
+                const int i = mfma_row(vv, l);
+                if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + nb * 32 + (l & 31)] = s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// prefill expand: y[tok, d] += sum_j V[pos, j] * Bpage_j[d] for a tile of up to 64 tokens and
+// up to 256 columns; wavefront w owns columns 64w .. 64w+63 (two 32-column blocks) and keeps
+// a 64 x 64 fp32 tile of y in its accumulators: y is loaded INTO the accumulators, the MFMAs
+// add onto it, and it is stored once, 128 contiguous bytes per token row and instruction.
+//
+// The first operand is V (tokens x ranks, fp32 in memory).  So that no precision is lost to
+// the 16-bit operand format it is split into 16-bit pieces whose sum is V: hi + lo for
+// binary16 (22+ bits), hi + mid + lo by truncation for bfloat16 (exactly 24 bits); each piece
+// costs one more MFMA on a path that is bound by memory, not by the matrix cores.
+// The second operand needs, per lane, 8 consecutive ranks of ONE column, but a page is
+// contiguous along columns; the wavefront therefore copies a 32-rank x 64-column slab of B
+// through LDS, transposing on the way in (two ranks packed per dword), and reads its operand
+// back with one 16-byte LDS load.  Each wavefront uses only its own LDS slab, so the
+// workgroup needs no barrier.
+// ---------------------------------------------------------------------------------------
+constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
+
+template <int DT>
+__device__ __forceinline__ void split_v(const f32x4 &lo4, const f32x4 &hi4, u32x4 (&piece)[3])
+{
+    float f[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+    if constexpr (DT == SLORA_F16) {
+        f16x8 a, b;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            a[e] = (_Float16)f[e];
+            b[e] = (_Float16)(f[e] - (float)a[e]);
+        }
+        piece[0] = __builtin_bit_cast(u32x4, a);
+        piece[1] = __builtin_bit_cast(u32x4, b);
+    } else {
+        uint32_t p0[8], p1[8], p2[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t h = __float_as_uint(f[e]) & 0xffff0000u;
+            const float r1 = f[e] - __uint_as_float(h);
+            const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
+            const float r2 = r1 - __uint_as_float(m);
+            p0[e] = h >> 16;
+            p1[e] = m >> 16;
+            p2[e] = __float_as_uint(r2) >> 16;
+        }
+        piece[0] = u32x4{p0[0] | (p0[1] << 16), p0[2] | (p0[3] << 16), p0[4] | (p0[5] << 16), p0[6] | (p0[7] << 16)};
+        piece[1] = u32x4{p1[0] | (p1[1] << 16), p1[2] | (p1[3] << 16), p1[4] | (p1[5] << 16), p1[6] | (p1[7] << 16)};
+        piece[2] = u32x4{p2[0] | (p2[1] << 16), p2[2] | (p2[3] << 16), p2[4] | (p2[5] << 16), p2[6] | (p2[7] << 16)};
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *__restrict__ items,
+                                                                    const int32_t *__restrict__ arena,
+                                                                    const uint16_t *__restrict__ pool,
+                                                                    const int32_t *__restrict__ tok_idx, int H,
+                                                                    int v_stride, MultiArgs args)
+{
+    __shared__ u32x4 slab_mem[4][64 * kSlabStride / 4];
+    const Item it = items[blockIdx.x];
+    const int cs = blockIdx.y;
+    float *__restrict__ y = args.y[cs];
+    const float *__restrict__ v = args.v[cs];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int n = lane & 31;
+    const int q = lane >> 5;
+    const int col_end = it.a + it.b;        // <= H
+    const int colw = it.a + wave * 64;      // this wavefront's first column
+    if (colw >= col_end) return;            // no barrier is used below
+    uint32_t *slab = reinterpret_cast<uint32_t *>(slab_mem[wave]);
+    const int32_t *pbl = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
+    constexpr int NP = DT == SLORA_F16 ? 2 : 3;
+
+    // accumulators start as the y tile
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+            const int i = mb * 32 + mfma_row(vv, lane);
+            const bool r_ok = i < it.ntok;
+            const int64_t base = r_ok ? (int64_t)tok_idx[it.pos0 + i] * H : 0;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int c = colw + nb * 32 + n;
+                acc[mb][nb][vv] = (r_ok && c < col_end) ? y[base + c] : 0.f;
+            }
+        }
+
+    const int cg = lane & 7;   // column group (8 columns) this lane copies
+    const int kp = lane >> 3;  // rank pair this lane copies
+    const int col8 = colw + 8 * cg;
+    const bool c_ok = col8 < col_end;
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    const float *vrow[2];
+    bool v_ok[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        v_ok[mb] = mb * 32 + n < it.ntok;
+        vrow[mb] = v + (int64_t)(it.pos0 + (v_ok[mb] ? mb * 32 + n : 0)) * v_stride;
+    }
+
+    for (int k0 = 0; k0 < it.rank; k0 += 32) {
+        // ---- B slab: ranks k0..k0+31 x this wavefront's 64 columns, transposed into LDS
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int ka = k0 + 16 * rd + 2 * kp;
+            u32x4 wa = zero, wb = zero;
+            if (c_ok && ka < it.rank) wa = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pbl[ka] * H + col8);
+            if (c_ok && ka + 1 < it.rank) wb = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pbl[ka + 1] * H + col8);
+            uint32_t *dst = slab + (8 * cg) * kSlabStride + 8 * rd + kp;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dst[(2 * e) * kSlabStride] = (wa[e] & 0xffffu) | (wb[e] << 16);
+                dst[(2 * e + 1) * kSlabStride] = (wa[e] >> 16) | (wb[e] & 0xffff0000u);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int k = k0 + 16 * s + 8 * q;
+            u32x4 bop[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+                bop[nb] = *reinterpret_cast<const u32x4 *>(slab + (nb * 32 + n) * kSlabStride + 8 * s + 4 * q);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+                f32x4 f0 = f32x4{0.f, 0.f, 0.f, 0.f}, f1 = f0;
+                if (v_ok[mb]) {
+                    f0 = *reinterpret_cast<const f32x4 *>(vrow[mb] + k);
+                    f1 = *reinterpret_cast<const f32x4 *>(vrow[mb] + k + 4);
+                }
+                u32x4 piece[3];
+                split_v<DT>(f0, f1, piece);
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32<DT>(piece[p], bop[nb], acc[mb][nb]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+            const int i = mb * 32 + mfma_row(vv, lane);
+            if (i < it.ntok) {
+                const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const int c = colw + nb * 32 + n;
+                    if (c < col_end) y[base + c] = acc[mb][nb][vv];
+                }
+            }
+        }
+}
+
 int32_t check_launch(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -273,7 +554,6 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     slora_pool *pool = plan->pool;
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
-    if (!plan->ms_items.empty()) return fail(SLORA_EINVAL, "MFMA path is not available in this build");
     if (!plan->vs_items.empty()) {
         const dim3 grid((unsigned)plan->vs_items.size(), (unsigned)n);
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
@@ -286,6 +566,17 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         int32_t rc = check_launch("shrink_vec");
         if (rc != SLORA_OK) return rc;
     }
+    if (!plan->ms_items.empty()) {
+        const dim3 grid((unsigned)plan->ms_items.size(), (unsigned)n);
+        if (pool->dtype == SLORA_F16)
+            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
+                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        else
+            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_BF16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
+                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        int32_t rc = check_launch("shrink_mfma");
+        if (rc != SLORA_OK) return rc;
+    }
     return SLORA_OK;
 }
 
@@ -294,7 +585,6 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     slora_pool *pool = plan->pool;
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
-    if (!plan->me_items.empty()) return fail(SLORA_EINVAL, "MFMA path is not available in this build");
     if (!plan->ve_items.empty()) {
         const dim3 grid((unsigned)plan->ve_items.size(), (unsigned)n);
         if (pool->dtype == SLORA_F16)
@@ -304,6 +594,17 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
             hipLaunchKernelGGL(expand_vec_kernel<SLORA_BF16>, grid, dim3(kWave), 0, st, plan->d_ve, pool->d_arena, base,
                                plan->d_tok_idx, pool->H, plan->v_stride, args);
         int32_t rc = check_launch("expand_vec");
+        if (rc != SLORA_OK) return rc;
+    }
+    if (!plan->me_items.empty()) {
+        const dim3 grid((unsigned)plan->me_items.size(), (unsigned)n);
+        if (pool->dtype == SLORA_F16)
+            hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
+                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        else
+            hipLaunchKernelGGL(expand_mfma_kernel<SLORA_BF16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
+                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        int32_t rc = check_launch("expand_mfma");
         if (rc != SLORA_OK) return rc;
     }
     return SLORA_OK;

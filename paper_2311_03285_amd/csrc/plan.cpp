@@ -104,7 +104,12 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 plan->n_groups_mfma++;
                 for (int32_t p = 0; p < n; p += kMfmaTok) {
                     const int32_t nt = std::min(kMfmaTok, n - p);
-                    plan->ms_items.push_back(Item{off, g.rank, 0, 0, pos_base + p, nt, 0, 0});
+                    for (int32_t j = 0; j < g.rank; j += kMfmaRanks)
+                        plan->ms_items.push_back(
+                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, 0, 0});
+                }
+                for (int32_t p = 0; p < n; p += kMfmaExpandTok) {
+                    const int32_t nt = std::min(kMfmaExpandTok, n - p);
                     for (int32_t c = 0; c < H; c += kMfmaExpandCols)
                         plan->me_items.push_back(
                             Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, 0, 0});

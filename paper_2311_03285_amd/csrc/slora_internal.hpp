@@ -23,7 +23,7 @@ const char *last_error_cstr();
 // One record type serves the four work lists; `a` and `b` mean
 //   vector shrink : a = first page j0 of the A list, b = number of pages
 //   vector expand : a = first column (element index),  b = unused
-//   MFMA   shrink : a = unused,                         b = unused
+//   MFMA   shrink : a = first rank j0 (multiple of 128), b = number of ranks (<= 128)
 //   MFMA   expand : a = first column (element index),  b = number of columns
 struct Item {
     int32_t arena_off; // adapter's first entry in the page-list arena ([slot][A r][B r])
@@ -50,8 +50,10 @@ constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows stage
 constexpr int kShrinkPages = 8;   // pages per vector-shrink item
 constexpr int kExpandTok = 8;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandCols = 512;  // columns per vector-expand item (one wavefront x 8 elements)
-constexpr int kMfmaTok = 32;      // tokens per MFMA item (one 32-row MFMA block)
-constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item
+constexpr int kMfmaTok = 32;      // tokens per MFMA-shrink item (one 32-row MFMA block)
+constexpr int kMfmaRanks = 128;   // ranks per MFMA-shrink item (four 32-column MFMA blocks)
+constexpr int kMfmaExpandTok = 64;   // tokens per MFMA-expand item (two 32-row MFMA blocks)
+constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item (4 wavefronts x 64)
 constexpr int kRankPad = 32;      // v rows are zero-padded to a multiple of this many ranks
 
 // ---------------------------------------------------------------------------------------

@@ -1,0 +1,138 @@
+"""GPU parity of the MFMA (prefill) kernels and of the full-size configurations.
+
+Same tolerance as the decode tests: rel-L2 <= 1e-3 and max-abs <= 1e-2 against the fp64
+oracle; integer-valued inputs bit for bit.  The same batch is also forced through each of the
+two kernel families, which must both stay inside the tolerance.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2311_03285_amd import slora, synth
+from paper_2311_03285_amd.harness import DeviceWorkload
+from gpu_util import REL_L2_EXPECTED, assert_close, errors, gpu_slot, oracle_slot
+
+pytestmark = pytest.mark.gpu
+
+VEC_ONLY = 1 << 40
+MFMA_ALL = 1
+
+
+def prefill_workload(seed, dtype, H=1000, ranks=(1, 3, 0, 5, 17, 8, 64, 33, 128, 160), lens=(1, 2, 31, 32, 33, 64, 65, 100, 7, 130),
+                     n_slots=2, n_pages=1800, **kw):
+    """Segments of ragged lengths around the tile sizes (32 / 64 tokens), odd ranks, one rank
+    above 128 (two shrink rank chunks), a rank-0 adapter, and a few tokens without adapter."""
+    g = np.random.default_rng(seed)
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_ad = g.permutation(len(ranks))[:len(lens)]
+    ids = np.repeat(seg_ad, lens).astype(np.int32)
+    ids[seg[2]:seg[2] + 31] = -1                       # a whole segment without adapter
+    return synth.make_workload("prefill-ragged", seed, H, dtype, n_pages, n_slots, ranks, ids, seg, **kw)
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("H", [64, 1000, 4096])
+def test_forced_mfma_path(dtype, H):
+    w = prefill_workload(400 + H, dtype, H=H)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        assert info["groups_vec"] == 0 and info["groups_mfma"] > 0
+        for slot in range(w.n_slots):
+            got = gpu_slot(dw, slot, plan)
+            ref = oracle_slot(w, slot)
+            rel, mx = assert_close(got, ref, f"mfma H={H} slot={slot}")
+            assert rel <= 5e-6, rel
+            untouched = (w.ids < 0) | (w.ranks[np.maximum(w.ids, 0)] == 0)
+            assert np.array_equal(got[untouched], w.y_in(slot)[untouched])
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_both_paths_agree_with_the_oracle_on_the_same_batch(dtype):
+    w = prefill_workload(450, dtype, H=512, y_zero=True)
+    ref = oracle_slot(w, 0)
+    outs = {}
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        for name, thr in (("vec", VEC_ONLY), ("mfma", MFMA_ALL), ("mixed", 16)):
+            slora.set_option(dw.pool, "mfma_min_tokens", thr)
+            outs[name] = gpu_slot(dw, 0, dw.plan())
+            assert_close(outs[name], ref, name)
+    rel, _ = errors(outs["vec"], outs["mfma"].astype(np.float64))
+    assert rel <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_mfma_integer_inputs_are_bit_exact(dtype):
+    """Integer inputs: every product and partial sum is an integer below 2^22, so the 16-bit
+    pieces of v, the MFMA products and the fp32 accumulation are all exact."""
+    w = prefill_workload(460, dtype, H=512, int_valued=True)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        for slot in range(w.n_slots):
+            got = gpu_slot(dw, slot)
+            assert np.array_equal(got.astype(np.float64), oracle_slot(w, slot))
+
+
+def test_mfma_zero_B_and_determinism():
+    w = prefill_workload(470, synth.F16, H=512)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        plan = dw.plan()
+        a = gpu_slot(dw, 1, plan)
+        assert np.array_equal(a, gpu_slot(dw, 1, plan))
+        pages = np.concatenate([w.page_idx[k][0, 1] for k in range(w.n_adapters)])
+        slora.pool_write_pages(dw.pool, pages, np.zeros((pages.size, w.H), np.uint16), False)
+        yi = w.y_in(0)
+        yi[yi == 0] = 0.0
+        got = gpu_slot(dw, 0, plan, y_in=yi)
+        assert np.array_equal(got.view(np.uint32), yi.view(np.uint32))
+
+
+def test_mfma_multi_slot_matches_single_slot():
+    w = prefill_workload(480, synth.BF16, H=1000)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        plan = dw.plan()                                     # default threshold: both families
+        info = slora.plan_info(plan)
+        assert info["groups_vec"] > 0 and info["groups_mfma"] > 0
+        singles = [gpu_slot(dw, s, plan) for s in range(2)]
+        xs = [dw.x_dev(0), dw.x_dev(1)]
+        ys = [dw.y_dev(0), dw.y_dev(1)]
+        slora.lora_apply_multi(plan, [0, 1], [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+        torch.cuda.synchronize()
+        for s in range(2):
+            assert np.array_equal(ys[s].cpu().numpy(), singles[s])
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _full_config(n, slots, law="power"):
+    w = synth.config(n, law=law)
+    with DeviceWorkload(w, real_adapters="used", slots=slots) as dw:
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        for slot in slots:
+            got = gpu_slot(dw, slot, plan)
+            ref = oracle_slot(w, slot)
+            rel, mx = assert_close(got, ref, f"cfg{n} slot {slot}")
+            assert rel <= 5e-6, rel
+        # one adapter's pages, gathered back bit for bit from the scattered pool
+        a = int(w.used_adapters()[0])
+        assert np.array_equal(dw.gather(a, slots[0], 1), w.weight_bits(a, slots[0], 1))
+    return info
+
+
+def test_config3_prefill_full_size():
+    info = _full_config(3, [0, 3])
+    assert info["groups_mfma"] == info["groups"]            # every request is long enough for MFMA
+
+
+@pytest.mark.parametrize("law", ["power", "zipf"])
+def test_config4_large_pool_decode_full_size(law):
+    """115 GB pool (byte offsets beyond 2^32), 2000 adapters, everything else marked KV."""
+    info = _full_config(4, [0, 1, 2, 3], law)
+    assert info["tokens"] == 256
+
+
+def test_config5_mixed_full_size():
+    info = _full_config(5, [0, 15])
+    assert info["groups_mfma"] >= 8 and info["groups_vec"] > 100
