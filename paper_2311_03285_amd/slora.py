@@ -37,6 +37,12 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2311_03285_amd.build` "
                                     "(there is no CPU fallback)")
+        try:
+            # PyTorch ships its own HIP runtime; load it first so that this library binds to the
+            # same one (two runtimes in a process do not see each other's device state)
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         sig = {
