@@ -7,6 +7,8 @@
 // plan's sorted token list.  All byte offsets into the pool are 64-bit.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "slora_internal.hpp"
 
 namespace slora {
@@ -16,6 +18,7 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 
@@ -87,15 +90,17 @@ __global__ __launch_bounds__(256) void gather_pages_kernel(const uint16_t *__res
 // decode path, shrink: v[pos, j] = sum_h x[tok, h] * Apage_j[h]
 //
 // One workgroup (4 wavefronts) = one item = up to kShrinkPages pages of one adapter and up to
-// kShrinkTok tokens that use it.  The tokens' x rows are staged once in LDS; each wavefront
-// then streams whole pages from HBM with 16-byte loads per lane (8 in flight), dots them
-// against the staged rows with packed 16-bit dot products accumulating in fp32, and reduces
-// across the 64 lanes.
+// kShrinkTok tokens that use it.  The tokens' x rows are staged once in LDS.  Each wavefront
+// streams whole pages from HBM (pages wave, wave+4, ... of the item) with 16-byte non-temporal
+// loads per lane, U loads per block, two blocks in flight (the next block - possibly of the
+// next page - is requested before the current one is consumed, and the very first block is
+// requested before x is staged).  Blocks are dotted against the staged rows with packed
+// 16-bit dot products accumulating in fp32; one 64-lane butterfly per page and token.
 // ---------------------------------------------------------------------------------------
 constexpr int kShrinkThreads = 256;
-constexpr int kShrinkUnroll = 8;
+constexpr int kShrinkWaves = kShrinkThreads / kWave;
 
-template <int DT>
+template <int DT, int U>
 __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *__restrict__ items,
                                                                      const int32_t *__restrict__ arena,
                                                                      const uint16_t *__restrict__ pool,
@@ -103,14 +108,60 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
                                                                      int v_stride, MultiArgs args)
 {
     extern __shared__ u32x4 xs[]; // [ntok][H/8]
-    const Item it = items[blockIdx.x];
-    const int cs = blockIdx.y;
+    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int nch = H >> 3; // 16-byte chunks per row
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
+    const int nblk = (nch + kWave * U - 1) / (kWave * U);                           // blocks per page
+    const int my_pages = it.b > wave ? (it.b - wave + kShrinkWaves - 1) / kShrinkWaves : 0;
+    const int total = my_pages * nblk;
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a + wave;
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+
+    // block `blk` of this wavefront's page number `pg`
+    auto load_block = [&](int pg, int blk, u32x4(&w)[U]) {
+        const u32x4 *page = reinterpret_cast<const u32x4 *>(pool + (int64_t)pa[pg * kShrinkWaves] * H);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = (blk * U + u) * kWave + lane;
+            w[u] = c < nch ? __builtin_nontemporal_load(page + c) : zero;
+        }
+    };
+    float acc[kShrinkTok];
+#pragma unroll
+    for (int t = 0; t < kShrinkTok; ++t) acc[t] = 0.f;
+    auto consume = [&](int pg, int blk, const u32x4(&w)[U]) {
+#pragma unroll
+        for (int t = 0; t < kShrinkTok; ++t) {
+            if (t < it.ntok) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = (blk * U + u) * kWave + lane;
+                    const u32x4 xv = c < nch ? xs[t * nch + c] : zero;
+                    acc[t] = dot8<DT>(w[u], xv, acc[t]);
+                }
+            }
+        }
+        if (blk == nblk - 1) {
+            const int j = it.a + wave + pg * kShrinkWaves;
+#pragma unroll
+            for (int t = 0; t < kShrinkTok; ++t) {
+                if (t < it.ntok) {
+                    const float s = wave_sum(acc[t]);
+                    if (lane == 0) v[(int64_t)(it.pos0 + t) * v_stride + j] = s;
+                }
+                acc[t] = 0.f;
+            }
+        }
+    };
+
+    u32x4 wa[U], wb[U];
+    if (total > 0) load_block(0, 0, wa);
 
     for (int t = 0; t < it.ntok; ++t) {
         const u32x4 *row = reinterpret_cast<const u32x4 *>(x + (int64_t)tok_idx[it.pos0 + t] * H);
@@ -118,112 +169,123 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
     }
     __syncthreads();
 
-    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank;
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    for (int jj = wave; jj < it.b; jj += kShrinkThreads / kWave) {
-        const int j = it.a + jj;
-        const u32x4 *page = reinterpret_cast<const u32x4 *>(pool + (int64_t)pa[j] * H);
-        float acc[kShrinkTok];
-#pragma unroll
-        for (int t = 0; t < kShrinkTok; ++t) acc[t] = 0.f;
-        for (int c0 = 0; c0 < nch; c0 += kWave * kShrinkUnroll) {
-            u32x4 w[kShrinkUnroll];
-#pragma unroll
-            for (int u = 0; u < kShrinkUnroll; ++u) {
-                const int c = c0 + u * kWave + lane;
-                w[u] = c < nch ? __builtin_nontemporal_load(page + c) : zero;
-            }
-#pragma unroll
-            for (int t = 0; t < kShrinkTok; ++t) {
-                if (t < it.ntok) {
-#pragma unroll
-                    for (int u = 0; u < kShrinkUnroll; ++u) {
-                        const int c = c0 + u * kWave + lane;
-                        const u32x4 xv = c < nch ? xs[t * nch + c] : zero;
-                        acc[t] = dot8<DT>(w[u], xv, acc[t]);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < kShrinkTok; ++t) {
-            if (t < it.ntok) {
-                const float s = wave_sum(acc[t]);
-                if (lane == 0) v[(int64_t)(it.pos0 + t) * v_stride + j] = s;
-            }
-        }
+    int pg = 0, blk = 0;       // position of the block held in wa
+    for (int b = 0; b < total; b += 2) {
+        int pg1 = pg, blk1 = blk + 1;
+        if (blk1 == nblk) { blk1 = 0; ++pg1; }
+        if (b + 1 < total) load_block(pg1, blk1, wb);
+        consume(pg, blk, wa);
+        int pg2 = pg1, blk2 = blk1 + 1;
+        if (blk2 == nblk) { blk2 = 0; ++pg2; }
+        if (b + 2 < total) load_block(pg2, blk2, wa);
+        if (b + 1 < total) consume(pg1, blk1, wb);
+        pg = pg2;
+        blk = blk2;
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // decode path, expand: y[tok, d] += sum_j v[pos, j] * Bpage_j[d]
 //
-// One wavefront = one item = 512 columns of one adapter's B for up to kExpandTok tokens.  Each
-// lane owns 8 adjacent columns: it streams 16 bytes of every B row (8 rows in flight), widens
-// to fp32 and accumulates v[pos, j] * row for every token, then does one read-modify-write of
-// its 8 floats of y per token (a wavefront covers 2 KiB of a y row).
+// One workgroup = one item = a run of columns (a multiple of 512, up to 4096) of one adapter's
+// B for up to kExpandTok tokens.  Each lane owns 8 adjacent columns, adjacent wavefronts own
+// adjacent 1 KiB pieces of every B row, so a workgroup reads each row as one contiguous run
+// of several KiB.  Rows are streamed with 16-byte non-temporal loads, U rows per block, two
+// blocks in flight, widened to fp32 and accumulated as v[pos, j] * row for every token (v is
+// wave-uniform and comes in through scalar loads); then one read-modify-write of y per token,
+// whose loads are issued before the row loop when there are at most two tokens.
 // ---------------------------------------------------------------------------------------
-constexpr int kExpandUnroll = 8;
-
-template <int DT>
-__global__ __launch_bounds__(kWave) void expand_vec_kernel(const Item *__restrict__ items,
-                                                            const int32_t *__restrict__ arena,
-                                                            const uint16_t *__restrict__ pool,
-                                                            const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                            MultiArgs args)
+template <int DT, int TOK, int U, bool PREFETCH_Y>
+__device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *__restrict__ pb,
+                                                const uint16_t *__restrict__ pool,
+                                                const int32_t *__restrict__ tok_idx, int H, int v_stride,
+                                                float *__restrict__ y, const float *__restrict__ v, int col, bool live)
 {
-    const Item it = items[blockIdx.x];
-    const int cs = blockIdx.y;
-    float *__restrict__ y = args.y[cs];
-    const float *__restrict__ v = args.v[cs];
-    const int lane = threadIdx.x;
-    const int col = it.a + lane * 8;
-    const bool live = col < H;
-    const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
+    const int lane = threadIdx.x & (kWave - 1);
     const float *vrow = v + (int64_t)it.pos0 * v_stride;
-
-    float acc[kExpandTok][8];
+    float acc[TOK][8];
 #pragma unroll
-    for (int t = 0; t < kExpandTok; ++t)
+    for (int t = 0; t < TOK; ++t)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
 
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    for (int j0 = 0; j0 < it.rank; j0 += kExpandUnroll) {
-        u32x4 w[kExpandUnroll];
+    f32x4 y0[TOK], y1[TOK];
+    float *yp[TOK];
 #pragma unroll
-        for (int u = 0; u < kExpandUnroll; ++u) {
-            const int j = j0 + u;
-            w[u] = (j < it.rank && live)
-                       ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pool + (int64_t)pb[j] * H + col))
-                       : zero;
+    for (int t = 0; t < TOK; ++t) {
+        yp[t] = y + (int64_t)tok_idx[it.pos0 + (t < it.ntok ? t : 0)] * H + col;
+        if (PREFETCH_Y && t < it.ntok && live) {
+            y0[t] = *reinterpret_cast<const f32x4 *>(yp[t]);
+            y1[t] = *reinterpret_cast<const f32x4 *>(yp[t] + 4);
         }
+    }
+
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    // Ranks are taken in windows of 64: lane l first fetches the page index and the v values of
+    // rank w0 + l (one coalesced load each); inside the window both are broadcast with readlane,
+    // so the row loads of a block issue back to back with no dependent scalar loads between them.
+    for (int w0 = 0; w0 < it.rank; w0 += kWave) {
+        const int wr = min(kWave, it.rank - w0);
+        const int pwin = lane < wr ? pb[w0 + lane] : 0;
+        float vwin[TOK];
 #pragma unroll
-        for (int u = 0; u < kExpandUnroll; ++u) {
-            const int j = j0 + u;
-            if (j < it.rank) {
-                float f[8];
-                widen2<DT>(w[u].x, f[0], f[1]);
-                widen2<DT>(w[u].y, f[2], f[3]);
-                widen2<DT>(w[u].z, f[4], f[5]);
-                widen2<DT>(w[u].w, f[6], f[7]);
+        for (int t = 0; t < TOK; ++t) vwin[t] = (t < it.ntok && lane < wr) ? vrow[t * v_stride + w0 + lane] : 0.f;
+
+        auto load_block = [&](int j0, u32x4(&w)[U]) {
 #pragma unroll
-                for (int t = 0; t < kExpandTok; ++t) {
-                    if (t < it.ntok) {
-                        const float vv = vrow[t * v_stride + j];
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u;
+                w[u] = zero;
+                if (j < wr) {
+                    const int64_t page = __builtin_amdgcn_readlane(pwin, j);
+                    if (live) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pool + page * H + col));
+                }
+            }
+        };
+        auto consume = [&](int j0, const u32x4(&w)[U]) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(vv, f[e], acc[t][e]);
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u;
+                if (j < wr) {
+                    float f[8];
+                    widen2<DT>(w[u].x, f[0], f[1]);
+                    widen2<DT>(w[u].y, f[2], f[3]);
+                    widen2<DT>(w[u].z, f[4], f[5]);
+                    widen2<DT>(w[u].w, f[6], f[7]);
+#pragma unroll
+                    for (int t = 0; t < TOK; ++t) {
+                        if (t < it.ntok) {
+                            const float vv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vwin[t]), j));
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(vv, f[e], acc[t][e]);
+                        }
                     }
                 }
             }
+        };
+
+        u32x4 wa[U], wb[U];
+        load_block(0, wa);
+        for (int j0 = 0; j0 < wr; j0 += 2 * U) {
+            if (j0 + U < wr) load_block(j0 + U, wb);
+            consume(j0, wa);
+            if (j0 + 2 * U < wr) load_block(j0 + 2 * U, wa);
+            if (j0 + U < wr) consume(j0 + U, wb);
         }
     }
+
     if (!live) return;
 #pragma unroll
-    for (int t = 0; t < kExpandTok; ++t) {
+    for (int t = 0; t < TOK; ++t) {
         if (t < it.ntok) {
-            float4 *yp = reinterpret_cast<float4 *>(y + (int64_t)tok_idx[it.pos0 + t] * H + col);
-            float4 a = yp[0], b = yp[1];
+            f32x4 a, b;
+            if (PREFETCH_Y) {
+                a = y0[t];
+                b = y1[t];
+            } else {
+                a = *reinterpret_cast<const f32x4 *>(yp[t]);
+                b = *reinterpret_cast<const f32x4 *>(yp[t] + 4);
+            }
             a.x += acc[t][0];
             a.y += acc[t][1];
             a.z += acc[t][2];
@@ -232,11 +294,37 @@ __global__ __launch_bounds__(kWave) void expand_vec_kernel(const Item *__restric
             b.y += acc[t][5];
             b.z += acc[t][6];
             b.w += acc[t][7];
-            yp[0] = a;
-            yp[1] = b;
+            *reinterpret_cast<f32x4 *>(yp[t]) = a;
+            *reinterpret_cast<f32x4 *>(yp[t] + 4) = b;
         }
     }
 }
+
+template <int DT>
+__global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict__ items,
+                                                          const int32_t *__restrict__ arena,
+                                                          const uint16_t *__restrict__ pool,
+                                                          const int32_t *__restrict__ tok_idx, int H, int v_stride,
+                                                          MultiArgs args)
+{
+    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
+    const int col = it.a + threadIdx.x * 8;
+    const int col_end = it.a + it.b; // <= H; both are multiples of 8
+    // only WHOLE wavefronts beyond the item's columns may leave: the lanes of a wavefront exchange
+    // page indices and v through readlane, so every lane of a live wavefront must stay active
+    if (it.a + (int)(threadIdx.x & ~(kWave - 1)) * 8 >= col_end) return;
+    const bool live = col < col_end;
+    const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
+    if (it.ntok == 1)
+        expand_vec_body<DT, 1, 8, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+    else if (it.ntok == 2)
+        expand_vec_body<DT, 2, 8, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+    else
+        expand_vec_body<DT, kExpandTok, 4, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+}
+
 
 // ---------------------------------------------------------------------------------------
 // prefill path (MFMA).  Matrix blocks are 32 x 32 with 16 k-values per instruction
@@ -247,7 +335,6 @@ __global__ __launch_bounds__(kWave) void expand_vec_kernel(const Item *__restric
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int DT>
 __device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f32x16 &c)
@@ -287,8 +374,9 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
                                                                     int v_stride, MultiArgs args)
 {
     __shared__ float red[4][16][kWave];
-    const Item it = items[blockIdx.x];
-    const int cs = blockIdx.y;
+    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int tid = threadIdx.x;
@@ -415,8 +503,9 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
                                                                     int v_stride, MultiArgs args)
 {
     __shared__ u32x4 slab_mem[4][64 * kSlabStride / 4];
-    const Item it = items[blockIdx.x];
-    const int cs = blockIdx.y;
+    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
     float *__restrict__ y = args.y[cs];
     const float *__restrict__ v = args.v[cs];
     const int lane = threadIdx.x & (kWave - 1);
@@ -555,19 +644,35 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->vs_items.empty()) {
-        const dim3 grid((unsigned)plan->vs_items.size(), (unsigned)n);
+        const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
-        if (pool->dtype == SLORA_F16)
-            hipLaunchKernelGGL(shrink_vec_kernel<SLORA_F16>, grid, dim3(kShrinkThreads), lds, st, plan->d_vs,
-                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
-        else
-            hipLaunchKernelGGL(shrink_vec_kernel<SLORA_BF16>, grid, dim3(kShrinkThreads), lds, st, plan->d_vs,
-                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        // loads per block: as few blocks per page as 8 loads allow, then the smallest U that fits
+        const int per_lane = (pool->H / 8 + kWave - 1) / kWave;
+        const int nblk = (per_lane + 7) / 8;
+        const int U = std::max(4, (per_lane + nblk - 1) / nblk);
+#define SLORA_LAUNCH_SHRINK(DT, UU)                                                                              \
+    hipLaunchKernelGGL((shrink_vec_kernel<DT, UU>), grid, dim3(kShrinkThreads), lds, st, plan->d_vs, pool->d_arena, \
+                       base, plan->d_tok_idx, pool->H, plan->v_stride, args)
+#define SLORA_SHRINK_U(DT)                                \
+    switch (U) {                                          \
+    case 4: SLORA_LAUNCH_SHRINK(DT, 4); break;            \
+    case 5: SLORA_LAUNCH_SHRINK(DT, 5); break;            \
+    case 6: SLORA_LAUNCH_SHRINK(DT, 6); break;            \
+    case 7: SLORA_LAUNCH_SHRINK(DT, 7); break;            \
+    default: SLORA_LAUNCH_SHRINK(DT, 8); break;           \
+    }
+        if (pool->dtype == SLORA_F16) {
+            SLORA_SHRINK_U(SLORA_F16)
+        } else {
+            SLORA_SHRINK_U(SLORA_BF16)
+        }
+#undef SLORA_SHRINK_U
+#undef SLORA_LAUNCH_SHRINK
         int32_t rc = check_launch("shrink_vec");
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->ms_items.empty()) {
-        const dim3 grid((unsigned)plan->ms_items.size(), (unsigned)n);
+        const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -586,18 +691,18 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->ve_items.empty()) {
-        const dim3 grid((unsigned)plan->ve_items.size(), (unsigned)n);
+        const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
-            hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3(kWave), 0, st, plan->d_ve, pool->d_arena, base,
-                               plan->d_tok_idx, pool->H, plan->v_stride, args);
+            hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
+                               plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         else
-            hipLaunchKernelGGL(expand_vec_kernel<SLORA_BF16>, grid, dim3(kWave), 0, st, plan->d_ve, pool->d_arena, base,
-                               plan->d_tok_idx, pool->H, plan->v_stride, args);
+            hipLaunchKernelGGL(expand_vec_kernel<SLORA_BF16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
+                               plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         int32_t rc = check_launch("expand_vec");
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->me_items.empty()) {
-        const dim3 grid((unsigned)plan->me_items.size(), (unsigned)n);
+        const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);

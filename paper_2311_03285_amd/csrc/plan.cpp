@@ -92,6 +92,16 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         plan->max_shrink_tok = 0;
         int32_t max_rank = 0;
         const int32_t H = pool->H;
+        // vector-expand items: long runs of columns (several KiB of every B row are then read at
+        // once), halved while a launch would have fewer workgroups than the GPU has CUs
+        int32_t n_vec_groups = 0;
+        for (int32_t gi : order)
+            if ((int64_t)groups[(size_t)gi].toks.size() < pool->mfma_min_tokens) n_vec_groups++;
+        int32_t chunks = (H + kExpandColsMax - 1) / kExpandColsMax;
+        auto cols_of = [&](int32_t c) { return ((H + c - 1) / c + 511) / 512 * 512; };
+        while ((int64_t)n_vec_groups * chunks < 256 && cols_of(chunks) > 512) chunks *= 2;
+        const int32_t ecols = cols_of(chunks);
+        plan->expand_threads = ecols / 8;
         for (int32_t gi : order) {
             const Group &g = groups[(size_t)gi];
             const int32_t n = (int32_t)g.toks.size();
@@ -125,8 +135,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
                 for (int32_t p = 0; p < n; p += kExpandTok) {
                     const int32_t nt = std::min(kExpandTok, n - p);
-                    for (int32_t c = 0; c < H; c += kExpandCols)
-                        plan->ve_items.push_back(Item{off, g.rank, c, 0, pos_base + p, nt, 0, 0});
+                    for (int32_t c = 0; c < H; c += ecols)
+                        plan->ve_items.push_back(Item{off, g.rank, c, std::min(ecols, H - c), pos_base + p, nt, 0, 0});
                 }
             }
         }
@@ -217,6 +227,7 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
     if (!x) return fail(SLORA_EINVAL, "x is NULL");
     if (plan->T_act == 0) return SLORA_OK;
     MultiArgs a{};
+    a.n = n;
     for (int32_t k = 0; k < n; ++k) {
         if (!x[k]) return fail(SLORA_EINVAL, "x[%d] is NULL", k);
         if (reinterpret_cast<uintptr_t>(x[k]) & 15) return fail(SLORA_EINVAL, "x[%d] must be 16-byte aligned", k);
@@ -241,6 +252,7 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *cons
     if (!y) return fail(SLORA_EINVAL, "y is NULL");
     if (plan->T_act == 0) return SLORA_OK;
     MultiArgs a{};
+    a.n = n;
     for (int32_t k = 0; k < n; ++k) {
         if (!y[k]) return fail(SLORA_EINVAL, "y[%d] is NULL", k);
         if (reinterpret_cast<uintptr_t>(y[k]) & 15) return fail(SLORA_EINVAL, "y[%d] must be 16-byte aligned", k);

@@ -22,7 +22,7 @@ const char *last_error_cstr();
 // ---------------------------------------------------------------------------------------
 // One record type serves the four work lists; `a` and `b` mean
 //   vector shrink : a = first page j0 of the A list, b = number of pages
-//   vector expand : a = first column (element index),  b = unused
+//   vector expand : a = first column (element index),  b = number of columns
 //   MFMA   shrink : a = first rank j0 (multiple of 128), b = number of ranks (<= 128)
 //   MFMA   expand : a = first column (element index),  b = number of columns
 struct Item {
@@ -43,13 +43,14 @@ struct MultiArgs {
     float *y[SLORA_MAX_MULTI];
     float *v[SLORA_MAX_MULTI];
     int32_t slot[SLORA_MAX_MULTI];
+    int32_t n; // slots in this launch; workgroup b handles item b / n for slot entry b % n
 };
 
 // Tile constants the scheduler and the kernels must agree on.
 constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows staged in LDS)
-constexpr int kShrinkPages = 8;   // pages per vector-shrink item
+constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 8;     // tokens per vector-expand item (accumulators in registers)
-constexpr int kExpandCols = 512;  // columns per vector-expand item (one wavefront x 8 elements)
+constexpr int kExpandColsMax = 3072; // most columns per vector-expand item (a multiple of 512, <= 4096)
 constexpr int kMfmaTok = 32;      // tokens per MFMA-shrink item (one 32-row MFMA block)
 constexpr int kMfmaRanks = 128;   // ranks per MFMA-shrink item (four 32-column MFMA blocks)
 constexpr int kMfmaExpandTok = 64;   // tokens per MFMA-expand item (two 32-row MFMA blocks)
@@ -98,6 +99,7 @@ struct slora_plan {
     int32_t T_act = 0;    // tokens that have an adapter of rank > 0
     int32_t v_stride = 0; // floats per row of v
     int32_t max_shrink_tok = 0;
+    int32_t expand_threads = 64; // workgroup size of the vector expand (columns per item / 8)
     int64_t sum_rank = 0;
     int32_t n_groups = 0, n_groups_vec = 0, n_groups_mfma = 0;
 

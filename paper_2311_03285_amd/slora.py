@@ -20,7 +20,7 @@ PLAN_INFO_N = 10
 PLAN_INFO_KEYS = ("tokens", "groups", "groups_vec", "groups_mfma", "vec_shrink_items", "vec_expand_items",
                   "mfma_shrink_items", "mfma_expand_items", "v_stride", "sum_rank")
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libslora_hip.so")
+LIB_PATH = os.environ.get("SLORA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libslora_hip.so")
 _lib = None
 
 

@@ -120,8 +120,8 @@ def test_scheduler_groups_buckets_and_routes():
     assert info["groups_mfma"] == 1 and info["groups_vec"] == 3
     assert info["sum_rank"] == 8 + 64 + 16 + 64
     assert info["v_stride"] == 64
-    # vector path: adapter 1 (2 tokens, r=64): 8 page-chunks; adapter 2: 2; adapter 0: 1
-    assert info["vec_shrink_items"] == 8 + 2 + 1
+    # vector path, 4 pages per shrink item: adapter 1 (2 tokens, r=64): 16; adapter 2 (r=16): 4; adapter 0 (r=8): 2
+    assert info["vec_shrink_items"] == 16 + 4 + 2
     assert info["vec_expand_items"] == 3 * (1024 // 512)
     assert info["mfma_shrink_items"] == 2             # 40 tokens in tiles of 32
     assert info["mfma_expand_items"] == 1 * (1024 // 256)    # 40 tokens in tiles of 64
