@@ -109,8 +109,13 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
 {
     extern __shared__ u32x4 xs[]; // [ntok][H/8]
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+#ifdef EXP_GRID2D
+    const int cs = blockIdx.x;
+    const Item it = items[blockIdx.y];
+#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
+#endif
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int nch = H >> 3; // 16-byte chunks per row
@@ -220,7 +225,7 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
         }
     }
 
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    const int col_ld = live ? col : it.a;
     // Ranks are taken in windows of 64: lane l first fetches the page index and the v values of
     // rank w0 + l (one coalesced load each); inside the window both are broadcast with readlane,
     // so the row loads of a block issue back to back with no dependent scalar loads between them.
@@ -231,46 +236,42 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
 #pragma unroll
         for (int t = 0; t < TOK; ++t) vwin[t] = (t < it.ntok && lane < wr) ? vrow[t * v_stride + w0 + lane] : 0.f;
 
-        auto load_block = [&](int j0, u32x4(&w)[U]) {
+        // Straight-line blocks: rank indices beyond the window are clamped to its last rank (the
+        // row is loaded again, from cache) and meet v = 0; lanes beyond the item's columns read the
+        // item's first column and are dropped at the store.  No branch separates the U loads.
+        const int nb = (wr + U - 1) / U;
+        auto load_block = [&](int b, u32x4(&w)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int j = j0 + u;
-                w[u] = zero;
-                if (j < wr) {
-                    const int64_t page = __builtin_amdgcn_readlane(pwin, j);
-                    if (live) w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pool + page * H + col));
-                }
+                const int j = min(b * U + u, wr - 1);
+                const int64_t page = __builtin_amdgcn_readlane(pwin, j);
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(pool + page * H + col_ld));
             }
         };
-        auto consume = [&](int j0, const u32x4(&w)[U]) {
+        auto consume = [&](int b, const u32x4(&w)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int j = j0 + u;
-                if (j < wr) {
-                    float f[8];
-                    widen2<DT>(w[u].x, f[0], f[1]);
-                    widen2<DT>(w[u].y, f[2], f[3]);
-                    widen2<DT>(w[u].z, f[4], f[5]);
-                    widen2<DT>(w[u].w, f[6], f[7]);
+                const int j = b * U + u; // < 64: nb * U <= 64
+                float f[8];
+                widen2<DT>(w[u].x, f[0], f[1]);
+                widen2<DT>(w[u].y, f[2], f[3]);
+                widen2<DT>(w[u].z, f[4], f[5]);
+                widen2<DT>(w[u].w, f[6], f[7]);
 #pragma unroll
-                    for (int t = 0; t < TOK; ++t) {
-                        if (t < it.ntok) {
-                            const float vv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vwin[t]), j));
+                for (int t = 0; t < TOK; ++t) {
+                    if (t < it.ntok) {
+                        const float vv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vwin[t]), j));
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(vv, f[e], acc[t][e]);
-                        }
+                        for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(vv, f[e], acc[t][e]);
                     }
                 }
             }
         };
 
-        u32x4 wa[U], wb[U];
-        load_block(0, wa);
-        for (int j0 = 0; j0 < wr; j0 += 2 * U) {
-            if (j0 + U < wr) load_block(j0 + U, wb);
-            consume(j0, wa);
-            if (j0 + 2 * U < wr) load_block(j0 + 2 * U, wa);
-            if (j0 + U < wr) consume(j0 + U, wb);
+        u32x4 w[U];
+        for (int b = 0; b < nb; ++b) {
+            load_block(b, w);
+            consume(b, w);
         }
     }
 
@@ -308,21 +309,30 @@ __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict_
                                                           MultiArgs args)
 {
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+#ifdef EXP_GRID2D
+    const int cs = blockIdx.x;
+    const Item it = items[blockIdx.y];
+#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
+#endif
     const int col = it.a + threadIdx.x * 8;
     const int col_end = it.a + it.b; // <= H; both are multiples of 8
     // only WHOLE wavefronts beyond the item's columns may leave: the lanes of a wavefront exchange
     // page indices and v through readlane, so every lane of a live wavefront must stay active
     if (it.a + (int)(threadIdx.x & ~(kWave - 1)) * 8 >= col_end) return;
+#ifdef EXP_ALLLIVE
+    const bool live = true;
+#else
     const bool live = col < col_end;
+#endif
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
-        expand_vec_body<DT, 1, 8, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, 1, 16, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
     else if (it.ntok == 2)
-        expand_vec_body<DT, 2, 8, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, 2, 16, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
     else
-        expand_vec_body<DT, kExpandTok, 4, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, kExpandTok, 8, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
 }
 
 
@@ -375,8 +385,13 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
 {
     __shared__ float red[4][16][kWave];
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+#ifdef EXP_GRID2D
+    const int cs = blockIdx.x;
+    const Item it = items[blockIdx.y];
+#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
+#endif
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int tid = threadIdx.x;
@@ -504,8 +519,13 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
 {
     __shared__ u32x4 slab_mem[4][64 * kSlabStride / 4];
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+#ifdef EXP_GRID2D
+    const int cs = blockIdx.x;
+    const Item it = items[blockIdx.y];
+#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
+#endif
     float *__restrict__ y = args.y[cs];
     const float *__restrict__ v = args.v[cs];
     const int lane = threadIdx.x & (kWave - 1);
@@ -644,7 +664,11 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->vs_items.empty()) {
+        #ifdef EXP_GRID2D
+        const dim3 grid((unsigned)n, (unsigned)plan->vs_items.size());
+#else
         const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
+#endif
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
         // loads per block: as few blocks per page as 8 loads allow, then the smallest U that fits
         const int per_lane = (pool->H / 8 + kWave - 1) / kWave;
@@ -672,7 +696,11 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->ms_items.empty()) {
+        #ifdef EXP_GRID2D
+        const dim3 grid((unsigned)n, (unsigned)plan->ms_items.size());
+#else
         const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
+#endif
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -691,7 +719,11 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->ve_items.empty()) {
+        #ifdef EXP_GRID2D
+        const dim3 grid((unsigned)n, (unsigned)plan->ve_items.size());
+#else
         const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
+#endif
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
                                plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -702,7 +734,11 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->me_items.empty()) {
+        #ifdef EXP_GRID2D
+        const dim3 grid((unsigned)n, (unsigned)plan->me_items.size());
+#else
         const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
+#endif
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);

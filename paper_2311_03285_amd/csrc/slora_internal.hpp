@@ -49,7 +49,7 @@ struct MultiArgs {
 // Tile constants the scheduler and the kernels must agree on.
 constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows staged in LDS)
 constexpr int kShrinkPages = 4;   // pages per vector-shrink item
-constexpr int kExpandTok = 8;     // tokens per vector-expand item (accumulators in registers)
+constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandColsMax = 3072; // most columns per vector-expand item (a multiple of 512, <= 4096)
 constexpr int kMfmaTok = 32;      // tokens per MFMA-shrink item (one 32-row MFMA block)
 constexpr int kMfmaRanks = 128;   // ranks per MFMA-shrink item (four 32-column MFMA blocks)
