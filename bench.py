@@ -40,6 +40,7 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -69,6 +70,9 @@ def main() -> int:
     log(f"[bench] pool ready: {w0.name}, {w0.n_pages} pages x {w0.H} ({w0.n_pages * w0.H * 2 / 1e9:.1f} GB), "
         f"{w0.n_adapters} adapters, {n_slots} slots, setup {time.time() - t_setup:.1f}s")
 
+    for kv in args.opt:
+        k, v = kv.split("=")
+        slora.set_option(dw.pool, k, int(v))
     stream = torch.cuda.Stream(device=dev)
     plans, xs, ys = [], [], []
     for b, w in enumerate(wls):

@@ -109,13 +109,8 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
 {
     extern __shared__ u32x4 xs[]; // [ntok][H/8]
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
-#ifdef EXP_GRID2D
-    const int cs = blockIdx.x;
-    const Item it = items[blockIdx.y];
-#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
-#endif
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int nch = H >> 3; // 16-byte chunks per row
@@ -309,23 +304,14 @@ __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict_
                                                           MultiArgs args)
 {
     // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
-#ifdef EXP_GRID2D
-    const int cs = blockIdx.x;
-    const Item it = items[blockIdx.y];
-#else
     const int cs = blockIdx.x % args.n;
     const Item it = items[blockIdx.x / args.n];
-#endif
     const int col = it.a + threadIdx.x * 8;
     const int col_end = it.a + it.b; // <= H; both are multiples of 8
     // only WHOLE wavefronts beyond the item's columns may leave: the lanes of a wavefront exchange
     // page indices and v through readlane, so every lane of a live wavefront must stay active
     if (it.a + (int)(threadIdx.x & ~(kWave - 1)) * 8 >= col_end) return;
-#ifdef EXP_ALLLIVE
-    const bool live = true;
-#else
     const bool live = col < col_end;
-#endif
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
         expand_vec_body<DT, 1, 16, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
@@ -357,41 +343,117 @@ __device__ __forceinline__ f32x16 mfma32(const u32x4 &a, const u32x4 &b, const f
                                                        0, 0, 0);
 }
 
+// Workgroup -> (item, slot) for the MFMA work lists.  The scheduler lays these lists out in rows
+// of kXcds items, column k holding work of the k-th share of the batch; workgroups are handed
+// to the 8 XCDs round-robin by their linear id, so making the item's column the fastest-varying
+// part of the id keeps every share on one XCD (all tiles of an adapter then find its pages in
+// that XCD's L2).  Within a row the slots follow one another.
+__device__ __forceinline__ int mfma_item_of(unsigned bid, int n)
+{
+    const unsigned per_row = kXcds * (unsigned)n;
+    return (int)((bid / per_row) * kXcds + (bid % kXcds));
+}
+__device__ __forceinline__ int mfma_slot_of(unsigned bid, int n)
+{
+    return (int)((bid % (kXcds * (unsigned)n)) / kXcds);
+}
+
 // accumulator register v of lane `lane` holds this row of the 32 x 32 block
 __device__ __forceinline__ int mfma_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // ---------------------------------------------------------------------------------------
 // prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for a tile of up to 32 tokens of
-// one adapter and up to 128 of its ranks.
+// one adapter and up to 128 of its ranks (NB blocks of 32).
 //
-// The four wavefronts of a workgroup split H: wavefront w takes the 64-element slices
-// 64*(4c + w).  Inside a slice, lane (row, q = l/32) owns 64 contiguous bytes of its row
-// (x row for the first operand, A page for the second) and feeds them to four MFMAs 16 bytes
-// at a time; both operands use the same assignment of k-values, which is all the instruction
-// needs.  Operands go from global memory straight to registers: every 128-byte line of x and
-// of the pages is fetched by exactly two lanes of one load group.  The four partial tiles are
-// summed through LDS in a fixed order and written once (no atomics).  Ranks beyond the
-// adapter's own, up to the next multiple of 32, are written as zeros so that the expand can
-// read whole blocks.
+// The four wavefronts of a workgroup split H into 32-element slices, wavefront w taking
+// slices w, w+4, ...  Inside a slice, lane (row, q = l/32) owns 32 contiguous bytes of its row
+// (an x row for the first operand, an A page for the second) and feeds them to two MFMAs; both
+// operands use the same assignment of k-values, which is all the instruction needs.  Operands
+// go from global memory straight to registers, two slices in flight (the steady-state loop has
+// no branch between the loads of one slice and the MFMAs of the other).  Rows beyond the tile
+// and pages beyond the adapter's ranks are read from a valid row instead (their results are
+// not stored, or stored as zero).  The four partial tiles are summed through LDS in a fixed
+// order and written once (no atomics).  Ranks beyond the adapter's own, up to the next
+// multiple of 32, are written as zeros so that the expand can read whole blocks.
 // ---------------------------------------------------------------------------------------
 constexpr int kMfmaThreads = 256;
+constexpr int kSliceH = 32; // elements of H per wavefront and step
+constexpr int kMfmaBlocks = kMfmaRanks / 32; // 32-rank MFMA blocks per shrink item
+
+template <int DT, int NB>
+__device__ __forceinline__ void shrink_mfma_body(const Item &it, const uint16_t *__restrict__ xrow,
+                                                 const uint16_t *const (&prow)[kMfmaBlocks], int H, int wave, int q,
+                                                 f32x16 (&acc)[kMfmaBlocks])
+{
+    struct Slice {
+        u32x4 xa[2];
+        u32x4 pb[NB][2];
+    };
+    const int n_slices = (H + kSliceH - 1) / kSliceH;
+    const int n_full = H / kSliceH;                           // slices with all 32 elements
+    const int mine_full = n_full > wave ? (n_full - wave + 3) / 4 : 0;
+    auto load = [&](int i, Slice &s) {                        // i-th full slice of this wavefront
+        const int h = (i * 4 + wave) * kSliceH + 16 * q;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            s.xa[k] = *reinterpret_cast<const u32x4 *>(xrow + h + 8 * k);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) s.pb[nb][k] = *reinterpret_cast<const u32x4 *>(prow[nb] + h + 8 * k);
+        }
+    };
+    auto mma = [&](const Slice &s) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32<DT>(s.xa[k], s.pb[nb][k], acc[nb]);
+    };
+
+    Slice a, b;
+    int i = 0;
+    if (mine_full > 0) {
+        load(0, a);
+        for (; i + 2 < mine_full; i += 2) {
+            load(i + 1, b);
+            mma(a);
+            load(i + 2, a);
+            mma(b);
+        }
+        if (i + 1 < mine_full) {
+            load(i + 1, b);
+            mma(a);
+            mma(b);
+        } else {
+            mma(a);
+        }
+    }
+    // the ragged last slice (H not a multiple of 32) belongs to one wavefront; zero-fill it
+    if (n_slices > n_full && (n_full & 3) == wave) {
+        const int h = n_full * kSliceH + 16 * q;
+        const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+        Slice s;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const bool ok = h + 8 * k < H;
+            s.xa[k] = ok ? *reinterpret_cast<const u32x4 *>(xrow + h + 8 * k) : zero;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                s.pb[nb][k] = ok ? *reinterpret_cast<const u32x4 *>(prow[nb] + h + 8 * k) : zero;
+        }
+        mma(s);
+    }
+}
 
 template <int DT>
-__global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *__restrict__ items,
+__global__ __launch_bounds__(kMfmaThreads, 4) void shrink_mfma_kernel(const Item *__restrict__ items,
                                                                     const int32_t *__restrict__ arena,
                                                                     const uint16_t *__restrict__ pool,
                                                                     const int32_t *__restrict__ tok_idx, int H,
                                                                     int v_stride, MultiArgs args)
 {
     __shared__ float red[4][16][kWave];
-    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
-#ifdef EXP_GRID2D
-    const int cs = blockIdx.x;
-    const Item it = items[blockIdx.y];
-#else
-    const int cs = blockIdx.x % args.n;
-    const Item it = items[blockIdx.x / args.n];
-#endif
+    const int cs = mfma_slot_of(blockIdx.x, args.n);
+    const Item it = items[mfma_item_of(blockIdx.x, args.n)];
+    if (it.ntok == 0) return; // padding of a short per-XCD list
     const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
     float *__restrict__ v = args.v[cs];
     const int tid = threadIdx.x;
@@ -400,52 +462,32 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
     const int row = lane & 31;
     const int q = lane >> 5;
     const int j0 = it.a, nj = it.b;
-    const int nblk = (nj + 31) >> 5; // 1..4 blocks of 32 ranks
+    const int nblk = (nj + 31) >> 5; // 1..kMfmaBlocks blocks of 32 ranks
     const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + j0;
 
-    const bool x_ok = row < it.ntok;
-    const uint16_t *xrow = x + (x_ok ? (int64_t)tok_idx[it.pos0 + row] * H : 0);
-    bool p_ok[4];
-    const uint16_t *prow[4];
+    // rows beyond the tile / ranks beyond the adapter read a valid row; their results are dropped
+    const uint16_t *xrow = x + (int64_t)tok_idx[it.pos0 + (row < it.ntok ? row : 0)] * H;
+    const uint16_t *prow[kMfmaBlocks];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < kMfmaBlocks; ++nb) {
         const int j = nb * 32 + row;
-        p_ok[nb] = j < nj;
-        prow[nb] = pool + (p_ok[nb] ? (int64_t)pa[j] * H : 0);
+        prow[nb] = pool + (int64_t)pa[j < nj ? j : 0] * H;
     }
 
-    f32x16 acc[4];
+    f32x16 acc[kMfmaBlocks];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+    for (int nb = 0; nb < kMfmaBlocks; ++nb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
 
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    for (int h0 = wave * 64; h0 < H; h0 += 4 * 64) {
-        const int hl = h0 + 32 * q;
-        u32x4 xa[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int h = hl + 8 * s;
-            xa[s] = (x_ok && h < H) ? *reinterpret_cast<const u32x4 *>(xrow + h) : zero;
-        }
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            if (nb < nblk) {
-                u32x4 pb[4];
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int h = hl + 8 * s;
-                    pb[s] = (p_ok[nb] && h < H) ? *reinterpret_cast<const u32x4 *>(prow[nb] + h) : zero;
-                }
-#pragma unroll
-                for (int s = 0; s < 4; ++s) acc[nb] = mfma32<DT>(xa[s], pb[s], acc[nb]);
-            }
-        }
-    }
+    static_assert(kMfmaRanks == 32 * kMfmaBlocks, "rank chunk of the scheduler and of the kernel differ");
+    if (nblk == 1) shrink_mfma_body<DT, 1>(it, xrow, prow, H, wave, q, acc);
+    if constexpr (kMfmaBlocks >= 2) if (nblk == 2) shrink_mfma_body<DT, 2>(it, xrow, prow, H, wave, q, acc);
+    if constexpr (kMfmaBlocks >= 3) if (nblk == 3) shrink_mfma_body<DT, 3>(it, xrow, prow, H, wave, q, acc);
+    if constexpr (kMfmaBlocks >= 4) if (nblk == 4) shrink_mfma_body<DT, 4>(it, xrow, prow, H, wave, q, acc);
 
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < kMfmaBlocks; ++nb) {
         if (nb < nblk) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[nb][e];
@@ -454,7 +496,8 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
                 const int vv = e >> 6, l = e & 63;
                 const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
                 const int i = mfma_row(vv, l);
-                if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + nb * 32 + (l & 31)] = s;
+                const int jn = nb * 32 + (l & 31);
+                if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + jn] = jn < nj ? s : 0.f;
             }
             __syncthreads();
         }
@@ -462,10 +505,12 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
 }
 
 // ---------------------------------------------------------------------------------------
-// prefill expand: y[tok, d] += sum_j V[pos, j] * Bpage_j[d] for a tile of up to 64 tokens and
-// up to 256 columns; wavefront w owns columns 64w .. 64w+63 (two 32-column blocks) and keeps
-// a 64 x 64 fp32 tile of y in its accumulators: y is loaded INTO the accumulators, the MFMAs
-// add onto it, and it is stored once, 128 contiguous bytes per token row and instruction.
+// prefill expand: y[tok, d] += sum_j V[pos, j] * Bpage_j[d] for a tile of up to 32 tokens and
+// up to 256 columns.  The four wavefronts of a workgroup are independent: wavefront w owns
+// columns 64w .. 64w+63 (two 32-column MFMA blocks) and keeps a 32 x 64 fp32 tile of y in its
+// accumulators - y is loaded INTO the accumulators, the MFMAs add onto it, and it is stored
+// once, 128 contiguous bytes per token row and instruction.  Many small independent tiles
+// (up to 20 wavefronts per CU) rather than deep software pipelines hide the memory latency.
 //
 // The first operand is V (tokens x ranks, fp32 in memory).  So that no precision is lost to
 // the 16-bit operand format it is split into 16-bit pieces whose sum is V: hi + lo for
@@ -475,7 +520,10 @@ __global__ __launch_bounds__(kMfmaThreads) void shrink_mfma_kernel(const Item *_
 // contiguous along columns; the wavefront therefore copies a 32-rank x 64-column slab of B
 // through LDS, transposing on the way in (two ranks packed per dword), and reads its operand
 // back with one 16-byte LDS load.  Each wavefront uses only its own LDS slab, so the
-// workgroup needs no barrier.
+// workgroup needs no barrier.  All global loads are unconditional: token rows beyond the
+// tile, columns beyond the item and ranks beyond the adapter's are redirected to a valid
+// row / column / page; what they produce is multiplied by the zero padding of V or is never
+// stored.
 // ---------------------------------------------------------------------------------------
 constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
 
@@ -518,70 +566,67 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
                                                                     int v_stride, MultiArgs args)
 {
     __shared__ u32x4 slab_mem[4][64 * kSlabStride / 4];
-    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
-#ifdef EXP_GRID2D
-    const int cs = blockIdx.x;
-    const Item it = items[blockIdx.y];
-#else
-    const int cs = blockIdx.x % args.n;
-    const Item it = items[blockIdx.x / args.n];
-#endif
+    const int cs = mfma_slot_of(blockIdx.x, args.n);
+    const Item it = items[mfma_item_of(blockIdx.x, args.n)];
+    if (it.ntok == 0) return; // padding of a short per-XCD list
     float *__restrict__ y = args.y[cs];
     const float *__restrict__ v = args.v[cs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int n = lane & 31;
     const int q = lane >> 5;
-    const int col_end = it.a + it.b;        // <= H
+    const int col_end = it.a + it.b;        // <= H, multiple of 8
     const int colw = it.a + wave * 64;      // this wavefront's first column
-    if (colw >= col_end) return;            // no barrier is used below
+    if (colw >= col_end) return;            // whole wavefront; no barrier is used below
     uint32_t *slab = reinterpret_cast<uint32_t *>(slab_mem[wave]);
     const int32_t *pbl = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     constexpr int NP = DT == SLORA_F16 ? 2 : 3;
 
-    // accumulators start as the y tile
-    f32x16 acc[2][2];
+    // accumulators start as the y tile (rows / columns outside the tile read a valid element)
+    f32x16 acc[2];
+    int ccol[2];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int nb = 0; nb < 2; ++nb) ccol[nb] = min(colw + nb * 32 + n, col_end - 1);
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-            const int i = mb * 32 + mfma_row(vv, lane);
-            const bool r_ok = i < it.ntok;
-            const int64_t base = r_ok ? (int64_t)tok_idx[it.pos0 + i] * H : 0;
+    for (int vv = 0; vv < 16; ++vv) {
+        const int i = mfma_row(vv, lane);
+        const int64_t base = (int64_t)tok_idx[it.pos0 + (i < it.ntok ? i : 0)] * H;
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int c = colw + nb * 32 + n;
-                acc[mb][nb][vv] = (r_ok && c < col_end) ? y[base + c] : 0.f;
-            }
-        }
+        for (int nb = 0; nb < 2; ++nb) acc[nb][vv] = y[base + ccol[nb]];
+    }
 
     const int cg = lane & 7;   // column group (8 columns) this lane copies
     const int kp = lane >> 3;  // rank pair this lane copies
-    const int col8 = colw + 8 * cg;
-    const bool c_ok = col8 < col_end;
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    const float *vrow[2];
-    bool v_ok[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        v_ok[mb] = mb * 32 + n < it.ntok;
-        vrow[mb] = v + (int64_t)(it.pos0 + (v_ok[mb] ? mb * 32 + n : 0)) * v_stride;
-    }
+    const int col8 = min(colw + 8 * cg, col_end - 8);
+    const float *vrow = v + (int64_t)(it.pos0 + (n < it.ntok ? n : 0)) * v_stride;
 
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
+        // ---- operands of this stage: two B rows per lane and round, V for both k-steps
+        u32x4 wa[2], wb[2];
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int ka = k0 + 16 * rd + 2 * kp;
+            const int pa_ = pbl[min(ka, it.rank - 1)];
+            const int pb_ = pbl[min(ka + 1, it.rank - 1)];
+            wa[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pa_ * H + col8);
+            wb[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pb_ * H + col8);
+        }
+        f32x4 vf[2][2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int k = k0 + 16 * s + 8 * q;
+            vf[s][0] = *reinterpret_cast<const f32x4 *>(vrow + k);
+            vf[s][1] = *reinterpret_cast<const f32x4 *>(vrow + k + 4);
+        }
         // ---- B slab: ranks k0..k0+31 x this wavefront's 64 columns, transposed into LDS
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
-            const int ka = k0 + 16 * rd + 2 * kp;
-            u32x4 wa = zero, wb = zero;
-            if (c_ok && ka < it.rank) wa = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pbl[ka] * H + col8);
-            if (c_ok && ka + 1 < it.rank) wb = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pbl[ka + 1] * H + col8);
             uint32_t *dst = slab + (8 * cg) * kSlabStride + 8 * rd + kp;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                dst[(2 * e) * kSlabStride] = (wa[e] & 0xffffu) | (wb[e] << 16);
-                dst[(2 * e + 1) * kSlabStride] = (wa[e] >> 16) | (wb[e] & 0xffff0000u);
+                dst[(2 * e) * kSlabStride] = (wa[rd][e] & 0xffffu) | (wb[rd][e] << 16);
+                dst[(2 * e + 1) * kSlabStride] = (wa[rd][e] >> 16) | (wb[rd][e] & 0xffff0000u);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -590,42 +635,31 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
 
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const int k = k0 + 16 * s + 8 * q;
             u32x4 bop[2];
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
                 bop[nb] = *reinterpret_cast<const u32x4 *>(slab + (nb * 32 + n) * kSlabStride + 8 * s + 4 * q);
+            u32x4 piece[3];
+            split_v<DT>(vf[s][0], vf[s][1], piece);
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                f32x4 f0 = f32x4{0.f, 0.f, 0.f, 0.f}, f1 = f0;
-                if (v_ok[mb]) {
-                    f0 = *reinterpret_cast<const f32x4 *>(vrow[mb] + k);
-                    f1 = *reinterpret_cast<const f32x4 *>(vrow[mb] + k + 4);
-                }
-                u32x4 piece[3];
-                split_v<DT>(f0, f1, piece);
+            for (int p = 0; p < NP; ++p)
 #pragma unroll
-                for (int p = 0; p < NP; ++p)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32<DT>(piece[p], bop[nb], acc[mb][nb]);
-            }
+                for (int nb = 0; nb < 2; ++nb) acc[nb] = mfma32<DT>(piece[p], bop[nb], acc[nb]);
         }
     }
 
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int vv = 0; vv < 16; ++vv) {
+        const int i = mfma_row(vv, lane);
+        if (i < it.ntok) {
+            const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-            const int i = mb * 32 + mfma_row(vv, lane);
-            if (i < it.ntok) {
-                const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const int c = colw + nb * 32 + n;
-                    if (c < col_end) y[base + c] = acc[mb][nb][vv];
-                }
+            for (int nb = 0; nb < 2; ++nb) {
+                const int c = colw + nb * 32 + n;
+                if (c < col_end) y[base + c] = acc[nb][vv];
             }
         }
+    }
 }
 
 int32_t check_launch(const char *what)
@@ -664,11 +698,7 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->vs_items.empty()) {
-        #ifdef EXP_GRID2D
-        const dim3 grid((unsigned)n, (unsigned)plan->vs_items.size());
-#else
-        const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
-#endif
+                const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
         // loads per block: as few blocks per page as 8 loads allow, then the smallest U that fits
         const int per_lane = (pool->H / 8 + kWave - 1) / kWave;
@@ -696,11 +726,7 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->ms_items.empty()) {
-        #ifdef EXP_GRID2D
-        const dim3 grid((unsigned)n, (unsigned)plan->ms_items.size());
-#else
-        const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
-#endif
+                const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -719,11 +745,7 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->ve_items.empty()) {
-        #ifdef EXP_GRID2D
-        const dim3 grid((unsigned)n, (unsigned)plan->ve_items.size());
-#else
-        const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
-#endif
+                const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
                                plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -734,11 +756,7 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->me_items.empty()) {
-        #ifdef EXP_GRID2D
-        const dim3 grid((unsigned)n, (unsigned)plan->me_items.size());
-#else
-        const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
-#endif
+                const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);

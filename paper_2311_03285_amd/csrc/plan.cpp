@@ -29,6 +29,40 @@ struct Group {
 
 int32_t hip_fail(hipError_t e, const char *what) { return fail(SLORA_EHIP, "%s: %s", what, hipGetErrorString(e)); }
 
+// Lay an MFMA work list out for the 8 XCDs.  The list arrives in group order (all items of an
+// adapter adjacent, adapters by descending rank).  It is cut into kXcds runs of about equal
+// cost (bytes moved), run k becomes column k of a row-major table with kXcds columns, short
+// columns are padded with empty items (ntok == 0).  The kernels map workgroup ids so that
+// column k runs on XCD k: the tiles of one adapter share an L2 and its pages are fetched
+// from HBM once per XCD instead of once per tile.  A big adapter may straddle two columns.
+template <class Cost>
+void xcd_layout(std::vector<Item> &items, Cost cost, bool group)
+{
+    if (items.empty()) return;
+    if (!group) { // plain order: consecutive items go to consecutive XCDs; pad the last row
+        items.resize((items.size() + kXcds - 1) / kXcds * kXcds, Item{0, 0, 0, 0, 0, 0, 0, 0});
+        return;
+    }
+    int64_t total = 0;
+    for (const Item &i : items) total += cost(i);
+    std::vector<std::vector<Item>> col((size_t)kXcds);
+    int64_t seen = 0;
+    for (const Item &i : items) {
+        // column of the item's midpoint in the running cost
+        const int64_t c = cost(i);
+        int k = (int)(((seen + c / 2) * kXcds) / std::max<int64_t>(total, 1));
+        k = std::min(std::max(k, 0), kXcds - 1);
+        col[(size_t)k].push_back(i);
+        seen += c;
+    }
+    size_t rows = 0;
+    for (const auto &c : col) rows = std::max(rows, c.size());
+    std::vector<Item> out(rows * (size_t)kXcds, Item{0, 0, 0, 0, 0, 0, 0, 0});
+    for (int k = 0; k < kXcds; ++k)
+        for (size_t r = 0; r < col[(size_t)k].size(); ++r) out[r * (size_t)kXcds + (size_t)k] = col[(size_t)k][r];
+    items.swap(out);
+}
+
 } // namespace
 
 int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids, int32_t T,
@@ -140,6 +174,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
             }
         }
+        xcd_layout(plan->ms_items, [H](const Item &i) { return (int64_t)(i.ntok + i.b) * H * 2; }, pool->xcd_group != 0);
+        xcd_layout(plan->me_items, [](const Item &i) { return (int64_t)i.b * (i.ntok * 8 + i.rank * 2); }, pool->xcd_group != 0);
         plan->T_act = (int32_t)plan->tok_idx.size();
         plan->v_stride = std::max(kRankPad, (max_rank + kRankPad - 1) / kRankPad * kRankPad);
     } catch (const std::bad_alloc &) {
@@ -313,14 +349,19 @@ int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n)
 {
     clear_error();
     if (!plan || !out || n < 0 || n > SLORA_PLAN_INFO_N) return fail(SLORA_EINVAL, "bad arguments");
+    auto live = [](const std::vector<Item> &l) { // without the padding of the per-XCD columns
+        int64_t c = 0;
+        for (const Item &i : l) c += i.ntok > 0;
+        return c;
+    };
     const int64_t v[SLORA_PLAN_INFO_N] = {plan->T_act,
                                           plan->n_groups,
                                           plan->n_groups_vec,
                                           plan->n_groups_mfma,
                                           (int64_t)plan->vs_items.size(),
                                           (int64_t)plan->ve_items.size(),
-                                          (int64_t)plan->ms_items.size(),
-                                          (int64_t)plan->me_items.size(),
+                                          live(plan->ms_items),
+                                          live(plan->me_items),
                                           plan->v_stride,
                                           plan->sum_rank};
     for (int32_t k = 0; k < n; ++k) out[k] = v[k];

@@ -315,6 +315,10 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
         pool->mfma_min_tokens = value;
         return SLORA_OK;
     }
+    if (!std::strcmp(key, "xcd_group")) {
+        pool->xcd_group = value != 0;
+        return SLORA_OK;
+    }
     return fail(SLORA_EINVAL, "unknown option '%s'", key);
 }
 

@@ -23,7 +23,7 @@ const char *last_error_cstr();
 // One record type serves the four work lists; `a` and `b` mean
 //   vector shrink : a = first page j0 of the A list, b = number of pages
 //   vector expand : a = first column (element index),  b = number of columns
-//   MFMA   shrink : a = first rank j0 (multiple of 128), b = number of ranks (<= 128)
+//   MFMA   shrink : a = first rank j0 (multiple of kMfmaRanks), b = number of ranks (<= kMfmaRanks)
 //   MFMA   expand : a = first column (element index),  b = number of columns
 struct Item {
     int32_t arena_off; // adapter's first entry in the page-list arena ([slot][A r][B r])
@@ -52,9 +52,10 @@ constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandColsMax = 3072; // most columns per vector-expand item (a multiple of 512, <= 4096)
 constexpr int kMfmaTok = 32;      // tokens per MFMA-shrink item (one 32-row MFMA block)
-constexpr int kMfmaRanks = 128;   // ranks per MFMA-shrink item (four 32-column MFMA blocks)
-constexpr int kMfmaExpandTok = 64;   // tokens per MFMA-expand item (two 32-row MFMA blocks)
+constexpr int kMfmaRanks = 64;    // ranks per MFMA-shrink item (two 32-column MFMA blocks)
+constexpr int kMfmaExpandTok = 32;   // tokens per MFMA-expand item (one 32-row MFMA block)
 constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item (4 wavefronts x 64)
+constexpr int kXcds = 8;         // accelerator dies (each with its own L2); MFMA lists are padded to this
 constexpr int kRankPad = 32;      // v rows are zero-padded to a multiple of this many ranks
 
 // ---------------------------------------------------------------------------------------
@@ -88,6 +89,7 @@ struct slora_pool {
     uint64_t unload_generation = 0;
     int64_t live_plans = 0;
     int64_t mfma_min_tokens = 16;
+    int64_t xcd_group = 0;
 
     int32_t sync_device();                            // push dirty arena range
 };

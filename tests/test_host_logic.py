@@ -124,7 +124,7 @@ def test_scheduler_groups_buckets_and_routes():
     assert info["vec_shrink_items"] == 16 + 4 + 2
     assert info["vec_expand_items"] == 3 * (1024 // 512)
     assert info["mfma_shrink_items"] == 2             # 40 tokens in tiles of 32
-    assert info["mfma_expand_items"] == 1 * (1024 // 256)    # 40 tokens in tiles of 64
+    assert info["mfma_expand_items"] == 2 * (1024 // 256)    # 40 tokens in tiles of 32
     slora.plan_destroy(plan)
     slora.set_option(p, "mfma_min_tokens", 1 << 40)
     plan = slora.batch_plan(p, ids, seg)
