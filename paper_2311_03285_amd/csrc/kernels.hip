@@ -363,145 +363,153 @@ __device__ __forceinline__ int mfma_row(int v, int lane) { return 8 * (v >> 2) +
 
 // ---------------------------------------------------------------------------------------
 // prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for a tile of up to 32 tokens of
-// one adapter and up to 128 of its ranks (NB blocks of 32).
+// one adapter and up to 64 of its ranks (one or two MFMA blocks of 32).
 //
-// The four wavefronts of a workgroup split H into 32-element slices, wavefront w taking
-// slices w, w+4, ...  Inside a slice, lane (row, q = l/32) owns 32 contiguous bytes of its row
-// (an x row for the first operand, an A page for the second) and feeds them to two MFMAs; both
-// operands use the same assignment of k-values, which is all the instruction needs.  Operands
-// go from global memory straight to registers, two slices in flight (the steady-state loop has
-// no branch between the loads of one slice and the MFMAs of the other).  Rows beyond the tile
-// and pages beyond the adapter's ranks are read from a valid row instead (their results are
-// not stored, or stored as zero).  The four partial tiles are summed through LDS in a fixed
-// order and written once (no atomics).  Ranks beyond the adapter's own, up to the next
-// multiple of 32, are written as zeros so that the expand can read whole blocks.
+// A classic LDS-tiled product with the second operand gathered through the page list.  H is
+// walked in chunks of 128 elements.  Per chunk the workgroup copies the 32 x-rows and the up to
+// 64 page rows (256 bytes of each) into LDS with fully coalesced 16-byte loads - 16 adjacent
+// lanes read one row's 256 bytes, so a wavefront instruction touches 8 cache lines instead of
+// the 32 a load in MFMA operand layout would - through a register ring that keeps three chunks
+// in flight per workgroup.  LDS rows are padded by 16 bytes; the four wavefronts take two of
+// the chunk's eight 16-element k-steps each, read their operands in MFMA layout with 16-byte
+// LDS loads and accumulate full 32 x 64 partial tiles, which are summed through LDS in a fixed
+// order at the end and written once (no atomics).  Token rows beyond the tile and ranks
+// beyond the adapter's are read from a valid row instead; their results are not stored, or
+// stored as zero (ranks up to the next multiple of 32, so the expand can read whole blocks).
 // ---------------------------------------------------------------------------------------
 constexpr int kMfmaThreads = 256;
-constexpr int kSliceH = 32; // elements of H per wavefront and step
-constexpr int kMfmaBlocks = kMfmaRanks / 32; // 32-rank MFMA blocks per shrink item
+constexpr int kMfmaBlocks = kMfmaRanks / 32;     // 32-rank MFMA blocks per shrink item
+constexpr int kChunkH = 128;                     // elements of H per chunk
+constexpr int kChunkBytes = kChunkH * 2;         // bytes of one row per chunk
+constexpr int kLdsRow = kChunkBytes + 16;        // padded LDS row
+constexpr int kTileRows = 32 + kMfmaRanks;       // x rows, then page rows
+constexpr int kRing = 3;                         // chunks in flight
+constexpr int kRowsPerPass = kMfmaThreads / 16;  // rows covered by one load per thread
+constexpr int kLoadsX = 32 / kRowsPerPass;       // x rows copied per thread (2)
 
 template <int DT, int NB>
-__device__ __forceinline__ void shrink_mfma_body(const Item &it, const uint16_t *__restrict__ xrow,
-                                                 const uint16_t *const (&prow)[kMfmaBlocks], int H, int wave, int q,
-                                                 f32x16 (&acc)[kMfmaBlocks])
+__device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *__restrict__ pa,
+                                                 const unsigned char *__restrict__ x,
+                                                 const uint16_t *__restrict__ pool,
+                                                 const int32_t *__restrict__ tok_idx, int H, int v_stride,
+                                                 float *__restrict__ v, unsigned char *lds)
 {
-    struct Slice {
-        u32x4 xa[2];
-        u32x4 pb[NB][2];
-    };
-    const int n_slices = (H + kSliceH - 1) / kSliceH;
-    const int n_full = H / kSliceH;                           // slices with all 32 elements
-    const int mine_full = n_full > wave ? (n_full - wave + 3) / 4 : 0;
-    auto load = [&](int i, Slice &s) {                        // i-th full slice of this wavefront
-        const int h = (i * 4 + wave) * kSliceH + 16 * q;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            s.xa[k] = *reinterpret_cast<const u32x4 *>(xrow + h + 8 * k);
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) s.pb[nb][k] = *reinterpret_cast<const u32x4 *>(prow[nb] + h + 8 * k);
-        }
-    };
-    auto mma = [&](const Slice &s) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32<DT>(s.xa[k], s.pb[nb][k], acc[nb]);
-    };
-
-    Slice a, b;
-    int i = 0;
-    if (mine_full > 0) {
-        load(0, a);
-        for (; i + 2 < mine_full; i += 2) {
-            load(i + 1, b);
-            mma(a);
-            load(i + 2, a);
-            mma(b);
-        }
-        if (i + 1 < mine_full) {
-            load(i + 1, b);
-            mma(a);
-            mma(b);
-        } else {
-            mma(a);
-        }
-    }
-    // the ragged last slice (H not a multiple of 32) belongs to one wavefront; zero-fill it
-    if (n_slices > n_full && (n_full & 3) == wave) {
-        const int h = n_full * kSliceH + 16 * q;
-        const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-        Slice s;
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const bool ok = h + 8 * k < H;
-            s.xa[k] = ok ? *reinterpret_cast<const u32x4 *>(xrow + h + 8 * k) : zero;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                s.pb[nb][k] = ok ? *reinterpret_cast<const u32x4 *>(prow[nb] + h + 8 * k) : zero;
-        }
-        mma(s);
-    }
-}
-
-template <int DT>
-__global__ __launch_bounds__(kMfmaThreads, 4) void shrink_mfma_kernel(const Item *__restrict__ items,
-                                                                    const int32_t *__restrict__ arena,
-                                                                    const uint16_t *__restrict__ pool,
-                                                                    const int32_t *__restrict__ tok_idx, int H,
-                                                                    int v_stride, MultiArgs args)
-{
-    __shared__ float red[4][16][kWave];
-    const int cs = mfma_slot_of(blockIdx.x, args.n);
-    const Item it = items[mfma_item_of(blockIdx.x, args.n)];
-    if (it.ntok == 0) return; // padding of a short per-XCD list
-    const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
-    float *__restrict__ v = args.v[cs];
+    constexpr int kLoadsP = NB * 32 / kRowsPerPass; // page rows copied per thread (2 or 4)
+    constexpr int kLoads = kLoadsX + kLoadsP;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int row = lane & 31;
     const int q = lane >> 5;
     const int j0 = it.a, nj = it.b;
-    const int nblk = (nj + 31) >> 5; // 1..kMfmaBlocks blocks of 32 ranks
-    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + j0;
+    const int64_t row_bytes = (int64_t)H * 2;
 
-    // rows beyond the tile / ranks beyond the adapter read a valid row; their results are dropped
-    const uint16_t *xrow = x + (int64_t)tok_idx[it.pos0 + (row < it.ntok ? row : 0)] * H;
-    const uint16_t *prow[kMfmaBlocks];
+    // ---- copy duty of this thread: byte column cb of LDS rows r16 + 16*i (x rows 0..31, then pages)
+    const int r16 = tid >> 4;
+    const int cb = (tid & 15) * 16;
+    const unsigned char *src[kLoads];
 #pragma unroll
-    for (int nb = 0; nb < kMfmaBlocks; ++nb) {
-        const int j = nb * 32 + row;
-        prow[nb] = pool + (int64_t)pa[j < nj ? j : 0] * H;
+    for (int i = 0; i < kLoadsX; ++i) {
+        const int r = r16 + kRowsPerPass * i;
+        src[i] = x + (int64_t)tok_idx[it.pos0 + (r < it.ntok ? r : 0)] * row_bytes;
     }
-
-    f32x16 acc[kMfmaBlocks];
 #pragma unroll
-    for (int nb = 0; nb < kMfmaBlocks; ++nb)
+    for (int i = 0; i < kLoadsP; ++i) {
+        const int j = r16 + kRowsPerPass * i;
+        src[kLoadsX + i] = reinterpret_cast<const unsigned char *>(pool) + (int64_t)pa[j < nj ? j : 0] * row_bytes;
+    }
+    const int n_chunks = (H + kChunkH - 1) / kChunkH;
+
+    struct Regs {
+        u32x4 w[kLoads];
+    };
+    auto load = [&](int c, Regs &r) { // chunk c (clamped to the last one), bytes clamped into the row
+        const int cc = min(c, n_chunks - 1);
+        const int64_t off = min((int64_t)cc * kChunkBytes + cb, row_bytes - 16);
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) r.w[i] = *reinterpret_cast<const u32x4 *>(src[i] + off);
+    };
+    auto stash = [&](int c, const Regs &r) { // registers -> LDS buffer c & 1; bytes past the row become zero
+        unsigned char *buf = lds + (c & 1) * (kTileRows * kLdsRow);
+        const bool ok = (int64_t)c * kChunkBytes + cb < row_bytes;
+        const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i)
+            *reinterpret_cast<u32x4 *>(buf + (r16 + kRowsPerPass * i) * kLdsRow + cb) = ok ? r.w[i] : zero;
+    };
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
-
-    static_assert(kMfmaRanks == 32 * kMfmaBlocks, "rank chunk of the scheduler and of the kernel differ");
-    if (nblk == 1) shrink_mfma_body<DT, 1>(it, xrow, prow, H, wave, q, acc);
-    if constexpr (kMfmaBlocks >= 2) if (nblk == 2) shrink_mfma_body<DT, 2>(it, xrow, prow, H, wave, q, acc);
-    if constexpr (kMfmaBlocks >= 3) if (nblk == 3) shrink_mfma_body<DT, 3>(it, xrow, prow, H, wave, q, acc);
-    if constexpr (kMfmaBlocks >= 4) if (nblk == 4) shrink_mfma_body<DT, 4>(it, xrow, prow, H, wave, q, acc);
-
+    auto compute = [&](int c) { // this wavefront's two k-steps of chunk c
+        const unsigned char *buf = lds + (c & 1) * (kTileRows * kLdsRow);
 #pragma unroll
-    for (int nb = 0; nb < kMfmaBlocks; ++nb) {
-        if (nb < nblk) {
+        for (int k = 0; k < 2; ++k) {
+            const int kb = (2 * wave + k) * 32 + q * 16; // byte offset of this lane's 8 k-values in the row
+            const u32x4 xa = *reinterpret_cast<const u32x4 *>(buf + row * kLdsRow + kb);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[nb][e];
-            __syncthreads();
-            for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
-                const int vv = e >> 6, l = e & 63;
-                const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
-                const int i = mfma_row(vv, l);
-                const int jn = nb * 32 + (l & 31);
-                if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + jn] = jn < nj ? s : 0.f;
+            for (int nb = 0; nb < NB; ++nb) {
+                const u32x4 pb = *reinterpret_cast<const u32x4 *>(buf + (32 + nb * 32 + row) * kLdsRow + kb);
+                acc[nb] = mfma32<DT>(xa, pb, acc[nb]);
             }
+        }
+    };
+
+    // register ring: chunk c is copied to LDS while chunks c+1 .. c+kRing-1 are still in flight
+    // and chunk c+kRing is requested (chunks past the end re-read the last one and are dropped)
+    Regs ring[kRing];
+#pragma unroll
+    for (int d = 0; d < kRing; ++d) load(d, ring[d]);
+    const int n_rounds = (n_chunks + kRing - 1) / kRing;
+    for (int rd = 0; rd < n_rounds; ++rd) {
+#pragma unroll
+        for (int d = 0; d < kRing; ++d) {
+            const int c = rd * kRing + d;
+            stash(c, ring[d]);
+            load(c + kRing, ring[d]);
             __syncthreads();
+            if (c < n_chunks) compute(c);
         }
     }
+    __syncthreads();
+
+    float(*red)[16][kWave] = reinterpret_cast<float(*)[16][kWave]>(lds);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[nb][e];
+        __syncthreads();
+        for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
+            const int vv = e >> 6, l = e & 63;
+            const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
+            const int i = mfma_row(vv, l);
+            const int jn = nb * 32 + (l & 31);
+            if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + jn] = jn < nj ? s : 0.f;
+        }
+        __syncthreads();
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kMfmaThreads, 3) void shrink_mfma_kernel(const Item *__restrict__ items,
+                                                                       const int32_t *__restrict__ arena,
+                                                                       const uint16_t *__restrict__ pool,
+                                                                       const int32_t *__restrict__ tok_idx, int H,
+                                                                       int v_stride, MultiArgs args)
+{
+    static_assert(kMfmaBlocks == 2 && kLoadsX == 2, "tile shape and thread mapping differ");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kTileRows * kLdsRow];
+    static_assert(sizeof(lds) >= 4 * 16 * kWave * sizeof(float), "reduction buffer must fit");
+    const int cs = mfma_slot_of(blockIdx.x, args.n);
+    const Item it = items[mfma_item_of(blockIdx.x, args.n)];
+    if (it.ntok == 0) return; // padding of a short per-XCD list
+    const unsigned char *x = static_cast<const unsigned char *>(args.x[cs]);
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a;
+    if (it.b <= 32)
+        shrink_mfma_tile<DT, 1>(it, pa, x, pool, tok_idx, H, v_stride, args.v[cs], lds);
+    else
+        shrink_mfma_tile<DT, 2>(it, pa, x, pool, tok_idx, H, v_stride, args.v[cs], lds);
 }
 
 // ---------------------------------------------------------------------------------------
