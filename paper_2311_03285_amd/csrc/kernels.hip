@@ -361,6 +361,40 @@ __device__ __forceinline__ int mfma_slot_of(unsigned bid, int n)
 // accumulator register v of lane `lane` holds this row of the 32 x 32 block
 __device__ __forceinline__ int mfma_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
+// v = x*A of the MFMA path is handed from shrink to expand already in the layout of the expand's
+// first MFMA operand, split into 16-bit pieces whose sum is the fp32 value (so nothing is lost to
+// the operand format): hi + lo for binary16 (22+ bits), hi + mid + lo by truncation for bfloat16
+// (exactly 24 bits).  One fragment = 64 lanes x 8 values (1 KiB) = the operand of one MFMA:
+// tokens 0..31 of the tile x ranks 16*kk .. 16*kk+15, lane = token + 32 * ((rank % 16) / 8).
+// Fragments are ordered [tile][kk][piece]; the expand reads each with one coalesced 16-byte load
+// per lane and does no conversion work.
+template <int DT>
+struct VPieces {
+    static constexpr int N = DT == SLORA_F16 ? 2 : 3;
+};
+__device__ __forceinline__ int64_t vfrag_index(int tile, int kk, int piece, int n_kk, int n_piece)
+{
+    return (((int64_t)tile * n_kk + kk) * n_piece + piece) * (kWave * 8);
+}
+template <int DT>
+__device__ __forceinline__ void split_store(float f, uint16_t *frag_base, int64_t piece_stride)
+{
+    if constexpr (DT == SLORA_F16) {
+        const _Float16 a = (_Float16)f;
+        const _Float16 b = (_Float16)(f - (float)a);
+        frag_base[0] = __builtin_bit_cast(uint16_t, a);
+        frag_base[piece_stride] = __builtin_bit_cast(uint16_t, b);
+    } else {
+        const uint32_t h = __float_as_uint(f) & 0xffff0000u;
+        const float r1 = f - __uint_as_float(h);
+        const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(m);
+        frag_base[0] = (uint16_t)(h >> 16);
+        frag_base[piece_stride] = (uint16_t)(m >> 16);
+        frag_base[2 * piece_stride] = (uint16_t)(__float_as_uint(r2) >> 16);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for a tile of up to 32 tokens of
 // one adapter and up to 64 of its ranks (one or two MFMA blocks of 32).
@@ -392,7 +426,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
                                                  const unsigned char *__restrict__ x,
                                                  const uint16_t *__restrict__ pool,
                                                  const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                 float *__restrict__ v, unsigned char *lds)
+                                                 uint16_t *__restrict__ vfrag, unsigned char *lds)
 {
     constexpr int kLoadsP = NB * 32 / kRowsPerPass; // page rows copied per thread (2 or 4)
     constexpr int kLoads = kLoadsX + kLoadsP;
@@ -485,7 +519,11 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
             const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
             const int i = mfma_row(vv, l);
             const int jn = nb * 32 + (l & 31);
-            if (i < it.ntok) v[(int64_t)(it.pos0 + i) * v_stride + j0 + jn] = jn < nj ? s : 0.f;
+            const int j = j0 + jn; // rank; ranks past the adapter's own are stored as zero
+            constexpr int NP = VPieces<DT>::N;
+            uint16_t *dst = vfrag + vfrag_index(it.tile, j >> 4, 0, v_stride >> 4, NP) +
+                            (i + 32 * ((j & 15) >> 3)) * 8 + (j & 7);
+            if (i < it.ntok) split_store<DT>(jn < nj ? s : 0.f, dst, kWave * 8);
         }
         __syncthreads();
     }
@@ -506,10 +544,11 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void shrink_mfma_kernel(const Item
     if (it.ntok == 0) return; // padding of a short per-XCD list
     const unsigned char *x = static_cast<const unsigned char *>(args.x[cs]);
     const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a;
+    uint16_t *vfrag = reinterpret_cast<uint16_t *>(args.v[cs] + args.vfrag_off);
     if (it.b <= 32)
-        shrink_mfma_tile<DT, 1>(it, pa, x, pool, tok_idx, H, v_stride, args.v[cs], lds);
+        shrink_mfma_tile<DT, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
     else
-        shrink_mfma_tile<DT, 2>(it, pa, x, pool, tok_idx, H, v_stride, args.v[cs], lds);
+        shrink_mfma_tile<DT, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -536,37 +575,6 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void shrink_mfma_kernel(const Item
 constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
 
 template <int DT>
-__device__ __forceinline__ void split_v(const f32x4 &lo4, const f32x4 &hi4, u32x4 (&piece)[3])
-{
-    float f[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
-    if constexpr (DT == SLORA_F16) {
-        f16x8 a, b;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            a[e] = (_Float16)f[e];
-            b[e] = (_Float16)(f[e] - (float)a[e]);
-        }
-        piece[0] = __builtin_bit_cast(u32x4, a);
-        piece[1] = __builtin_bit_cast(u32x4, b);
-    } else {
-        uint32_t p0[8], p1[8], p2[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t h = __float_as_uint(f[e]) & 0xffff0000u;
-            const float r1 = f[e] - __uint_as_float(h);
-            const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
-            const float r2 = r1 - __uint_as_float(m);
-            p0[e] = h >> 16;
-            p1[e] = m >> 16;
-            p2[e] = __float_as_uint(r2) >> 16;
-        }
-        piece[0] = u32x4{p0[0] | (p0[1] << 16), p0[2] | (p0[3] << 16), p0[4] | (p0[5] << 16), p0[6] | (p0[7] << 16)};
-        piece[1] = u32x4{p1[0] | (p1[1] << 16), p1[2] | (p1[3] << 16), p1[4] | (p1[5] << 16), p1[6] | (p1[7] << 16)};
-        piece[2] = u32x4{p2[0] | (p2[1] << 16), p2[2] | (p2[3] << 16), p2[4] | (p2[5] << 16), p2[6] | (p2[7] << 16)};
-    }
-}
-
-template <int DT>
 __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *__restrict__ items,
                                                                     const int32_t *__restrict__ arena,
                                                                     const uint16_t *__restrict__ pool,
@@ -578,7 +586,6 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
     const Item it = items[mfma_item_of(blockIdx.x, args.n)];
     if (it.ntok == 0) return; // padding of a short per-XCD list
     float *__restrict__ y = args.y[cs];
-    const float *__restrict__ v = args.v[cs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int n = lane & 31;
@@ -588,7 +595,9 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
     if (colw >= col_end) return;            // whole wavefront; no barrier is used below
     uint32_t *slab = reinterpret_cast<uint32_t *>(slab_mem[wave]);
     const int32_t *pbl = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
-    constexpr int NP = DT == SLORA_F16 ? 2 : 3;
+    constexpr int NP = VPieces<DT>::N;
+    const int n_kk = v_stride >> 4;
+    const u32x4 *vfrag = reinterpret_cast<const u32x4 *>(args.v[cs] + args.vfrag_off) + lane;
 
     // accumulators start as the y tile (rows / columns outside the tile read a valid element)
     f32x16 acc[2];
@@ -606,7 +615,6 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
     const int cg = lane & 7;   // column group (8 columns) this lane copies
     const int kp = lane >> 3;  // rank pair this lane copies
     const int col8 = min(colw + 8 * cg, col_end - 8);
-    const float *vrow = v + (int64_t)(it.pos0 + (n < it.ntok ? n : 0)) * v_stride;
 
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
         // ---- operands of this stage: two B rows per lane and round, V for both k-steps
@@ -619,13 +627,12 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
             wa[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pa_ * H + col8);
             wb[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pb_ * H + col8);
         }
-        f32x4 vf[2][2];
+        u32x4 piece[2][NP];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int k = k0 + 16 * s + 8 * q;
-            vf[s][0] = *reinterpret_cast<const f32x4 *>(vrow + k);
-            vf[s][1] = *reinterpret_cast<const f32x4 *>(vrow + k + 4);
-        }
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                piece[s][p] = vfrag[vfrag_index(it.tile, (k0 >> 4) + s, p, n_kk, NP) / 8];
         // ---- B slab: ranks k0..k0+31 x this wavefront's 64 columns, transposed into LDS
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -647,12 +654,10 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
                 bop[nb] = *reinterpret_cast<const u32x4 *>(slab + (nb * 32 + n) * kSlabStride + 8 * s + 4 * q);
-            u32x4 piece[3];
-            split_v<DT>(vf[s][0], vf[s][1], piece);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb) acc[nb] = mfma32<DT>(piece[p], bop[nb], acc[nb]);
+                for (int nb = 0; nb < 2; ++nb) acc[nb] = mfma32<DT>(piece[s][p], bop[nb], acc[nb]);
         }
     }
 

@@ -123,6 +123,7 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         plan->sum_rank = 0;
         plan->n_groups = (int32_t)order.size();
         plan->n_groups_vec = plan->n_groups_mfma = 0;
+        plan->n_mfma_tiles = 0;
         plan->max_shrink_tok = 0;
         int32_t max_rank = 0;
         const int32_t H = pool->H;
@@ -146,17 +147,16 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
             const int32_t off = (int32_t)g.arena_off;
             if ((int64_t)n >= pool->mfma_min_tokens) {
                 plan->n_groups_mfma++;
+                static_assert(kMfmaTok == kMfmaExpandTok, "shrink and expand share the v tiles");
                 for (int32_t p = 0; p < n; p += kMfmaTok) {
                     const int32_t nt = std::min(kMfmaTok, n - p);
+                    const int32_t tile = plan->n_mfma_tiles++;
                     for (int32_t j = 0; j < g.rank; j += kMfmaRanks)
                         plan->ms_items.push_back(
-                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, 0, 0});
-                }
-                for (int32_t p = 0; p < n; p += kMfmaExpandTok) {
-                    const int32_t nt = std::min(kMfmaExpandTok, n - p);
+                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, tile, 0});
                     for (int32_t c = 0; c < H; c += kMfmaExpandCols)
                         plan->me_items.push_back(
-                            Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, 0, 0});
+                            Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, tile, 0});
                 }
             } else {
                 plan->n_groups_vec++;
@@ -227,7 +227,7 @@ int32_t slora_plan::upload()
 
 int32_t slora_plan::ensure_v(int32_t n)
 {
-    const int64_t need = (int64_t)n * T_act * v_stride;
+    const int64_t need = (int64_t)n * v_slot_floats(pool->dtype);
     if (need <= d_v_cap) return SLORA_OK;
     hipError_t e = hipSuccess;
     if (d_v) {
@@ -277,7 +277,8 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
         rc = plan->ensure_v(n);
     }
     if (rc != SLORA_OK) return rc;
-    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->T_act * plan->v_stride;
+    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
+    a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
     rc = launch_shrink(plan, n, a, stream);
     if (rc == SLORA_OK) plan->v_slots = n;
     return rc;
@@ -301,7 +302,8 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *cons
         return fail(SLORA_EINVAL, "expand of %d slot(s) needs a preceding shrink of %d slot(s)", n, n);
     hipError_t e = hipSetDevice(plan->pool->device);
     if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
-    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->T_act * plan->v_stride;
+    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
+    a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
     return launch_expand(plan, n, a, stream);
 }
 

@@ -32,7 +32,7 @@ struct Item {
     int32_t b;
     int32_t pos0;      // first position in the sorted token list (also the row of v)
     int32_t ntok;      // tokens handled by this item
-    int32_t pad0;
+    int32_t tile;      // MFMA lists: number of the (adapter, 32-token) tile, shared by shrink and expand
     int32_t pad1;
 };
 static_assert(sizeof(Item) == 32, "Item must stay 32 bytes");
@@ -44,6 +44,7 @@ struct MultiArgs {
     float *v[SLORA_MAX_MULTI];
     int32_t slot[SLORA_MAX_MULTI];
     int32_t n; // slots in this launch; workgroup b handles item b / n for slot entry b % n
+    int64_t vfrag_off; // floats from v[k] to the slot's v tiles in MFMA operand layout
 };
 
 // Tile constants the scheduler and the kernels must agree on.
@@ -101,6 +102,7 @@ struct slora_plan {
     int32_t T_act = 0;    // tokens that have an adapter of rank > 0
     int32_t v_stride = 0; // floats per row of v
     int32_t max_shrink_tok = 0;
+    int32_t n_mfma_tiles = 0;
     int32_t expand_threads = 64; // workgroup size of the vector expand (columns per item / 8)
     int64_t sum_rank = 0;
     int32_t n_groups = 0, n_groups_vec = 0, n_groups_mfma = 0;
@@ -114,7 +116,12 @@ struct slora_plan {
     int32_t *d_tok_idx = nullptr;
     slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_ms = nullptr, *d_me = nullptr;
 
-    float *d_v = nullptr; // scratch for v = x*A, n * T_act * v_stride floats
+    float *d_v = nullptr; // scratch for v = x*A: per slot T_act * v_stride floats (vector path rows),
+                          // then n_mfma_tiles * (v_stride/16) * pieces KiB of MFMA operand fragments
+    int64_t v_slot_floats(int32_t dtype) const
+    {
+        return (int64_t)T_act * v_stride + (int64_t)n_mfma_tiles * (v_stride / 16) * (dtype == SLORA_F16 ? 2 : 3) * 256;
+    }
     int64_t d_v_cap = 0;
     int32_t v_slots = 0;  // n of the latest shrink
 
