@@ -711,7 +711,7 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->vs_items.empty()) {
-                const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
+        const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
         // loads per block: as few blocks per page as 8 loads allow, then the smallest U that fits
         const int per_lane = (pool->H / 8 + kWave - 1) / kWave;
@@ -739,7 +739,7 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->ms_items.empty()) {
-                const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
+        const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -758,7 +758,7 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
     if (!plan->ve_items.empty()) {
-                const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
+        const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
                                plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
@@ -769,7 +769,7 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->me_items.empty()) {
-                const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
+        const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
         if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);

@@ -136,6 +136,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         auto cols_of = [&](int32_t c) { return ((H + c - 1) / c + 511) / 512 * 512; };
         while ((int64_t)n_vec_groups * chunks < 256 && cols_of(chunks) > 512) chunks *= 2;
         const int32_t ecols = cols_of(chunks);
+        // the vector shrink stages its tokens' x rows in LDS: at most 64 KiB of them per item
+        const int32_t shrink_tok = std::max(1, std::min(kShrinkTok, 65536 / (H * 2)));
         plan->expand_threads = ecols / 8;
         for (int32_t gi : order) {
             const Group &g = groups[(size_t)gi];
@@ -160,8 +162,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
             } else {
                 plan->n_groups_vec++;
-                for (int32_t p = 0; p < n; p += kShrinkTok) {
-                    const int32_t nt = std::min(kShrinkTok, n - p);
+                for (int32_t p = 0; p < n; p += shrink_tok) {
+                    const int32_t nt = std::min(shrink_tok, n - p);
                     plan->max_shrink_tok = std::max(plan->max_shrink_tok, nt);
                     for (int32_t j = 0; j < g.rank; j += kShrinkPages)
                         plan->vs_items.push_back(

@@ -165,3 +165,35 @@ def test_empty_batch_and_all_tokens_without_adapter():
         p1 = dw.plan(ids=ids, seg_offsets=None)
         got = gpu_slot(dw, 0, p1)
         assert np.array_equal(got, w.y_in(0))
+
+
+# ------------------------------------------------------------------ extreme shapes
+@pytest.mark.parametrize("path", ["vec", "mfma"])
+def test_largest_page_size(path):
+    """H = 32768 (the largest page the pool accepts): one x row fills the 64 KiB the vector
+    shrink may stage, so multi-token groups are cut into single-token items."""
+    g = np.random.default_rng(7)
+    ranks = (8, 40)
+    ids = np.array([0, 1, 1, 0, 1, -1, 1, 1], dtype=np.int32)
+    w = synth.make_workload("max-H", 901, 32768, synth.F16, 128, 1, ranks, ids)
+    with DeviceWorkload(w, real_adapters="all") as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY if path == "vec" else 1)
+        got = gpu_slot(dw, 0)
+        rel, mx = assert_close(got, oracle_slot(w, 0), f"H=32768 {path}")
+        assert rel <= 5e-6
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("path", ["vec", "mfma"])
+def test_largest_rank(dtype, path):
+    """rank 1024 (the largest max_rank): 16 windows of 64 ranks in the vector expand, 16 rank
+    chunks in the MFMA shrink, 32 stages in the MFMA expand."""
+    lens = [3, 40]
+    ids = np.repeat([0, 1], lens).astype(np.int32)
+    seg = np.array([0, 3, 43], dtype=np.int32)
+    w = synth.make_workload("max-rank", 902, 256, dtype, 4200, 1, (1024, 1000), ids, seg)
+    with DeviceWorkload(w, real_adapters="all", max_rank=1024) as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY if path == "vec" else 1)
+        got = gpu_slot(dw, 0)
+        rel, mx = assert_close(got, oracle_slot(w, 0), f"rank 1024 {path}")
+        assert rel <= 5e-6
