@@ -23,6 +23,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the counter reads for the library's plain page-copy kernel of known size
+# (profiles/cfg4_decode_hbm_traffic.md); only for the default command line.
+MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 321874 * 1024,
+                                                                        "shrink_vec": 301755 * 1024}}
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
 
 
@@ -125,41 +130,45 @@ def main() -> int:
     flops_step = float(np.mean([w.flops() for w in wls])) * n_slots
     value = tok_per_step * args.steps / wall
 
-    # ---- per-kernel durations (HIP events on the launch stream), stage by stage ---------------
-    def stage_times(n_rep):
+    # ---- per-kernel durations: HIP events on the launch stream around runs of one stage ----------
+    # (the shrink of every rotating batch back to back, then the expand of every batch: each plan
+    # keeps its own v, and no event record sits between two launches of a run)
+    def stage_times(n_rounds):
         sh, ex = [], []
-        for i in range(n_rep):
-            b = i % R
-            p = plans[b]
+        for _ in range(n_rounds):
             for g0 in range(0, n_slots, slora.MAX_MULTI):
                 g = slots[g0:g0 + slora.MAX_MULTI]
                 ea, eb, ec = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 ea.record(stream)
-                slora.lora_shrink(p, g, [x_of(b, s) for s in g], stream)
+                for b in range(R):
+                    slora.lora_shrink(plans[b], g, [x_of(b, s) for s in g], stream)
                 eb.record(stream)
-                slora.lora_expand(p, g, [ys[b][s].data_ptr() for s in g], stream)
+                for b in range(R):
+                    slora.lora_expand(plans[b], g, [ys[b][s].data_ptr() for s in g], stream)
                 ec.record(stream)
-                sh.append((ea, eb, len(g), b))
-                ex.append((eb, ec, len(g), b))
+                sh.append((ea, eb, len(g)))
+                ex.append((eb, ec, len(g)))
         torch.cuda.synchronize()
-        f = lambda L: [(a.elapsed_time(b_) * 1e-3, n, b) for a, b_, n, b in L]
+        f = lambda L: [(a.elapsed_time(b_) * 1e-3 / R, n) for a, b_, n in L]
         return f(sh), f(ex)
 
-    stage_times(min(args.warmup, 8))
-    sh, ex = stage_times(max(8, min(args.steps, 64)))
-    sh_bytes = {b: wls[b].shrink_bytes() for b in range(R)}
-    ex_bytes = {b: wls[b].expand_bytes() for b in range(R)}
-    sh_t = float(np.mean([t for t, n, b in sh]))
-    ex_t = float(np.mean([t for t, n, b in ex]))
-    sh_gbs = float(np.mean([sh_bytes[b] * n / t for t, n, b in sh])) / 1e9
-    ex_gbs = float(np.mean([ex_bytes[b] * n / t for t, n, b in ex])) / 1e9
+    stage_times(2)
+    sh, ex = stage_times(max(2, min(args.steps // R, 16)))
+    sh_b = float(np.mean([w.shrink_bytes() for w in wls]))
+    ex_b = float(np.mean([w.expand_bytes() for w in wls]))
+    sh_t = float(np.mean([t for t, n in sh]))
+    ex_t = float(np.mean([t for t, n in ex]))
+    sh_gbs = float(np.mean([sh_b * n / t for t, n in sh])) / 1e9
+    ex_gbs = float(np.mean([ex_b * n / t for t, n in ex])) / 1e9
     dom = "expand" if ex_t >= sh_t else "shrink"
     dom_gbs = ex_gbs if dom == "expand" else sh_gbs
     kinds = ("mfma" if info["groups_mfma"] and not info["groups_vec"] else
              "vec" if not info["groups_mfma"] else "vec+mfma")
     roofline = {
         "bound": "hbm", "kernel": f"{dom}_{kinds}", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
-        "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+        "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC.get((w0.name, args.law, args.mode, R), {}).get(f"{dom}_{kinds}"),
+        "algorithmic_bytes_per_launch": int((ex_b if dom == "expand" else sh_b) * min(n_slots, slora.MAX_MULTI)),
         "avg_launch_us": round((ex_t if dom == "expand" else sh_t) * 1e6, 2),
         "other_kernel": {"kernel": f"{'shrink' if dom == 'expand' else 'expand'}_{kinds}",
                          "achieved": round(sh_gbs if dom == "expand" else ex_gbs, 1),
