@@ -172,7 +172,10 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  * Tuning knobs (affect plans made afterwards).  Keys:
  *   "mfma_min_tokens"  groups with at least this many tokens use the MFMA kernels
  *                      (default 16; 1 forces everything onto MFMA, a value > 2^30 disables it)
- * Unknown key: EINVAL.
+ *   "xcd_group"        0 (default): MFMA work items go to the 8 accelerator dies round-robin;
+ *                      1: each die gets a contiguous, equally heavy run of the list, so all tiles
+ *                      of an adapter share one L2 (fewer HBM reads, but measured slower here)
+ * Results never depend on these beyond floating-point summation order.  Unknown key: EINVAL.
  */
 int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value);
 

@@ -2,9 +2,10 @@
 // LoRA term (Sec. 5.3: gather matrix-vector for decode, gather matrix-matrix for prefill).
 //
 // Data layout: pool = n_pages rows of H 16-bit elements; an adapter's page lists sit in an
-// int32 arena as [slot][A columns r][B rows r]; x is T x H (16-bit), y is T x H (fp32),
-// v = x*A is kept in fp32 as rows of `v_stride` floats indexed by the token's position in the
-// plan's sorted token list.  All byte offsets into the pool are 64-bit.
+// int32 arena as [slot][A columns r][B rows r]; x is T x H (16-bit), y is T x H (fp32).
+// v = x*A keeps fp32 precision: the decode kernels store it as rows of `v_stride` floats indexed
+// by the token's position in the plan's sorted token list, the prefill kernels as 16-bit pieces
+// in MFMA operand order (see VPieces).  All byte offsets into the pool are 64-bit.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -136,3 +136,15 @@ def test_config4_large_pool_decode_full_size(law):
 def test_config5_mixed_full_size():
     info = _full_config(5, [0, 15])
     assert info["groups_mfma"] >= 8 and info["groups_vec"] > 100
+
+
+def test_xcd_grouping_changes_the_schedule_not_the_result():
+    w = prefill_workload(490, synth.F16, H=1000)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        a = gpu_slot(dw, 0, dw.plan())
+        slora.set_option(dw.pool, "xcd_group", 1)
+        p = dw.plan()
+        assert slora.plan_info(p)["mfma_shrink_items"] == slora.plan_info(dw.plans[0])["mfma_shrink_items"]
+        b = gpu_slot(dw, 0, p)
+        assert np.array_equal(a, b)

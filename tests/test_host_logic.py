@@ -130,5 +130,12 @@ def test_scheduler_groups_buckets_and_routes():
     plan = slora.batch_plan(p, ids, seg)
     assert slora.plan_info(plan)["groups_mfma"] == 0
     slora.plan_destroy(plan)
+    slora.set_option(p, "mfma_min_tokens", 16)
+    slora.set_option(p, "xcd_group", 1)
+    plan = slora.batch_plan(p, ids, seg)
+    grouped = slora.plan_info(plan)
+    assert grouped["mfma_shrink_items"] == 2 and grouped["mfma_expand_items"] == 2 * (1024 // 256)
+    slora.plan_destroy(plan)
     assert code(slora.set_option, p, "nope", 1) == slora.EINVAL
+    assert code(slora.set_option, p, "mfma_min_tokens", 0) == slora.EINVAL
     slora.pool_destroy(p)
