@@ -118,8 +118,9 @@ int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot,
  * seg_offsets == NULL: every token is its own segment (a pure decode batch); n_seg ignored.
  * id -1: the token has no adapter and its row of y is never touched.  Unknown id: ENOENT.
  * The plan groups tokens by adapter, orders groups by rank, routes small groups to the
- * matrix-vector kernels and large ones to the MFMA kernels, and can be applied to any slot,
- * any number of times, until an adapter is unloaded.  T == 0 is legal.
+ * matrix-vector kernels and large ones (when the batch has enough of them) to the MFMA
+ * kernels, and can be applied to any slot, any number of times, until an adapter is unloaded.
+ * T == 0 is legal.
  */
 int32_t slora_batch_plan(slora_pool *pool, slora_plan **out, const int32_t *token_adapter_ids,
                          int32_t T, const int32_t *seg_offsets, int32_t n_seg);
@@ -172,6 +173,9 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  * Tuning knobs (affect plans made afterwards).  Keys:
  *   "mfma_min_tokens"  groups with at least this many tokens use the MFMA kernels
  *                      (default 16; 1 forces everything onto MFMA, a value > 2^30 disables it)
+ *   "mfma_min_tiles"   the MFMA kernels are used only if such groups make up at least this many
+ *                      32-token tiles in the batch (default 32: fewer tiles cannot fill the GPU
+ *                      and run faster on the vector kernels)
  *   "xcd_group"        0 (default): MFMA work items go to the 8 accelerator dies round-robin;
  *                      1: each die gets a contiguous, equally heavy run of the list, so all tiles
  *                      of an adapter share one L2 (fewer HBM reads, but measured slower here)

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdint>
 #include <cstring>
 #include <new>
 
@@ -129,9 +130,18 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         const int32_t H = pool->H;
         // vector-expand items: long runs of columns (several KiB of every B row are then read at
         // once), halved while a launch would have fewer workgroups than the GPU has CUs
+        // The MFMA kernels pay off when adapters have many tokens AND there are enough 32-token
+        // tiles to fill the GPU: a handful of tiles is a few long, latency-bound workgroups, and
+        // such groups are faster on the vector path (their pages are re-read from L2).
+        int64_t mfma_tiles = 0;
+        for (int32_t gi : order) {
+            const int64_t n = (int64_t)groups[(size_t)gi].toks.size();
+            if (n >= pool->mfma_min_tokens) mfma_tiles += (n + kMfmaTok - 1) / kMfmaTok;
+        }
+        const int64_t min_tokens = mfma_tiles >= pool->mfma_min_tiles ? pool->mfma_min_tokens : INT64_MAX;
         int32_t n_vec_groups = 0;
         for (int32_t gi : order)
-            if ((int64_t)groups[(size_t)gi].toks.size() < pool->mfma_min_tokens) n_vec_groups++;
+            if ((int64_t)groups[(size_t)gi].toks.size() < min_tokens) n_vec_groups++;
         int32_t chunks = (H + kExpandColsMax - 1) / kExpandColsMax;
         auto cols_of = [&](int32_t c) { return ((H + c - 1) / c + 511) / 512 * 512; };
         while ((int64_t)n_vec_groups * chunks < 256 && cols_of(chunks) > 512) chunks *= 2;
@@ -147,7 +157,7 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
             plan->sum_rank += g.rank;
             max_rank = std::max(max_rank, g.rank);
             const int32_t off = (int32_t)g.arena_off;
-            if ((int64_t)n >= pool->mfma_min_tokens) {
+            if ((int64_t)n >= min_tokens) {
                 plan->n_groups_mfma++;
                 static_assert(kMfmaTok == kMfmaExpandTok, "shrink and expand share the v tiles");
                 for (int32_t p = 0; p < n; p += kMfmaTok) {

@@ -315,6 +315,11 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
         pool->mfma_min_tokens = value;
         return SLORA_OK;
     }
+    if (!std::strcmp(key, "mfma_min_tiles")) {
+        if (value < 1) return fail(SLORA_EINVAL, "mfma_min_tiles must be >= 1");
+        pool->mfma_min_tiles = value;
+        return SLORA_OK;
+    }
     if (!std::strcmp(key, "xcd_group")) {
         pool->xcd_group = value != 0;
         return SLORA_OK;

@@ -90,6 +90,7 @@ struct slora_pool {
     uint64_t unload_generation = 0;
     int64_t live_plans = 0;
     int64_t mfma_min_tokens = 16;
+    int64_t mfma_min_tiles = 32;
     int64_t xcd_group = 0;
 
     int32_t sync_device();                            // push dirty arena range

@@ -18,6 +18,13 @@ VEC_ONLY = 1 << 40
 MFMA_ALL = 1
 
 
+def route(pool, min_tokens, min_tiles=1):
+    """Choose the kernel family: groups of >= min_tokens tokens go to the MFMA kernels, provided
+    the batch has >= min_tiles 32-token tiles of them (1: no such condition)."""
+    slora.set_option(pool, "mfma_min_tokens", min_tokens)
+    slora.set_option(pool, "mfma_min_tiles", min_tiles)
+
+
 def prefill_workload(seed, dtype, H=1000, ranks=(1, 3, 0, 5, 17, 8, 64, 33, 128, 160), lens=(1, 2, 31, 32, 33, 64, 65, 100, 7, 130),
                      n_slots=2, n_pages=1800, **kw):
     """Segments of ragged lengths around the tile sizes (32 / 64 tokens), odd ranks, one rank
@@ -35,7 +42,7 @@ def prefill_workload(seed, dtype, H=1000, ranks=(1, 3, 0, 5, 17, 8, 64, 33, 128,
 def test_forced_mfma_path(dtype, H):
     w = prefill_workload(400 + H, dtype, H=H)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
-        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        route(dw.pool, MFMA_ALL)
         plan = dw.plan()
         info = slora.plan_info(plan)
         assert info["groups_vec"] == 0 and info["groups_mfma"] > 0
@@ -55,7 +62,7 @@ def test_both_paths_agree_with_the_oracle_on_the_same_batch(dtype):
     outs = {}
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
         for name, thr in (("vec", VEC_ONLY), ("mfma", MFMA_ALL), ("mixed", 16)):
-            slora.set_option(dw.pool, "mfma_min_tokens", thr)
+            route(dw.pool, thr)
             outs[name] = gpu_slot(dw, 0, dw.plan())
             assert_close(outs[name], ref, name)
     rel, _ = errors(outs["vec"], outs["mfma"].astype(np.float64))
@@ -68,7 +75,7 @@ def test_mfma_integer_inputs_are_bit_exact(dtype):
     pieces of v, the MFMA products and the fp32 accumulation are all exact."""
     w = prefill_workload(460, dtype, H=512, int_valued=True)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
-        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        route(dw.pool, MFMA_ALL)
         for slot in range(w.n_slots):
             got = gpu_slot(dw, slot)
             assert np.array_equal(got.astype(np.float64), oracle_slot(w, slot))
@@ -77,7 +84,7 @@ def test_mfma_integer_inputs_are_bit_exact(dtype):
 def test_mfma_zero_B_and_determinism():
     w = prefill_workload(470, synth.F16, H=512)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
-        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        route(dw.pool, MFMA_ALL)
         plan = dw.plan()
         a = gpu_slot(dw, 1, plan)
         assert np.array_equal(a, gpu_slot(dw, 1, plan))
@@ -92,7 +99,8 @@ def test_mfma_zero_B_and_determinism():
 def test_mfma_multi_slot_matches_single_slot():
     w = prefill_workload(480, synth.BF16, H=1000)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
-        plan = dw.plan()                                     # default threshold: both families
+        route(dw.pool, 16)                                   # both families
+        plan = dw.plan()
         info = slora.plan_info(plan)
         assert info["groups_vec"] > 0 and info["groups_mfma"] > 0
         singles = [gpu_slot(dw, s, plan) for s in range(2)]
@@ -141,7 +149,7 @@ def test_config5_mixed_full_size():
 def test_xcd_grouping_changes_the_schedule_not_the_result():
     w = prefill_workload(490, synth.F16, H=1000)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
-        slora.set_option(dw.pool, "mfma_min_tokens", MFMA_ALL)
+        route(dw.pool, MFMA_ALL)
         a = gpu_slot(dw, 0, dw.plan())
         slora.set_option(dw.pool, "xcd_group", 1)
         p = dw.plan()

@@ -178,6 +178,7 @@ def test_largest_page_size(path):
     w = synth.make_workload("max-H", 901, 32768, synth.F16, 128, 1, ranks, ids)
     with DeviceWorkload(w, real_adapters="all") as dw:
         slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY if path == "vec" else 1)
+        slora.set_option(dw.pool, "mfma_min_tiles", 1)
         got = gpu_slot(dw, 0)
         rel, mx = assert_close(got, oracle_slot(w, 0), f"H=32768 {path}")
         assert rel <= 5e-6
@@ -194,6 +195,7 @@ def test_largest_rank(dtype, path):
     w = synth.make_workload("max-rank", 902, 256, dtype, 4200, 1, (1024, 1000), ids, seg)
     with DeviceWorkload(w, real_adapters="all", max_rank=1024) as dw:
         slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY if path == "vec" else 1)
+        slora.set_option(dw.pool, "mfma_min_tiles", 1)
         got = gpu_slot(dw, 0)
         rel, mx = assert_close(got, oracle_slot(w, 0), f"rank 1024 {path}")
         assert rel <= 5e-6

@@ -111,6 +111,7 @@ def test_scheduler_groups_buckets_and_routes():
         slora.adapter_load(p, a, r, np.arange(at, at + 2 * r))
         at += 2 * r
     slora.set_option(p, "mfma_min_tokens", 16)
+    slora.set_option(p, "mfma_min_tiles", 1)
     ids = [0, 1, -1, 2, 3, 1, 0, 0] + [4] * 40
     seg = list(range(9)) + [48]
     plan = slora.batch_plan(p, ids, seg)
@@ -138,4 +139,9 @@ def test_scheduler_groups_buckets_and_routes():
     slora.plan_destroy(plan)
     assert code(slora.set_option, p, "nope", 1) == slora.EINVAL
     assert code(slora.set_option, p, "mfma_min_tokens", 0) == slora.EINVAL
+    # too few tiles to fill the GPU: the big group stays on the vector kernels
+    slora.set_option(p, "mfma_min_tiles", 3)
+    plan = slora.batch_plan(p, ids, seg)
+    assert slora.plan_info(plan)["groups_mfma"] == 0
+    slora.plan_destroy(plan)
     slora.pool_destroy(p)
