@@ -199,3 +199,41 @@ def test_largest_rank(dtype, path):
         got = gpu_slot(dw, 0)
         rel, mx = assert_close(got, oracle_slot(w, 0), f"rank 1024 {path}")
         assert rel <= 5e-6
+
+
+# ------------------------------------------------------------------ adapters come and go
+def test_unload_and_reload_reuses_pages_and_table_slots():
+    """Adapters are swapped between batches (the paper fetches the adapters of each batch into
+    the pool): after an unload the freed pages and the freed run of the page-list table are
+    taken by other adapters, old plans are refused, new plans see the new lists."""
+    import dataclasses
+    w = ragged_workload(307, synth.F16, H=512, ranks=(4, 16, 8, 16, 12), n_slots=1, n_pages=200)
+    with DeviceWorkload(w, real_adapters="all", mark_kv=False, max_rank=32) as dw:
+        old_plan = dw.plan()
+        before = gpu_slot(dw, 0, old_plan)
+        assert_close(before, oracle_slot(w, 0), "before the swap")
+        # adapter 1 (rank 16) leaves; adapter 3's twin 7 (rank 16: same table run length) and a
+        # rank-24 adapter 1 arrive on the freed pages plus fresh ones
+        freed = w.page_idx[1].reshape(-1)
+        slora.adapter_unload(dw.pool, 1)
+        with pytest.raises(slora.SloraError) as e:
+            slora.lora_apply(old_plan, 0, dw.x_dev(0).data_ptr(), dw.y_dev(0).data_ptr())
+        assert e.value.code == slora.EBUSY
+        used = set(int(p) for p in w.owned_pages())
+        fresh = [p for p in range(w.n_pages) if p not in used][:48 + 32 - freed.size]
+        pages = np.concatenate([freed, np.array(fresh, np.int32)]).astype(np.int32)
+        ranks2 = np.concatenate([w.ranks, [0, 0, 16]]).astype(np.int32)         # ids 5, 6 unused
+        ranks2[1] = 24
+        page_idx2 = list(w.page_idx) + [np.zeros((1, 2, 0), np.int32)] * 2 + [pages[48:80].reshape(1, 2, 16)]
+        page_idx2[1] = pages[:48].reshape(1, 2, 24)
+        ids2 = w.ids.copy()
+        ids2[ids2 == 3] = 7
+        w2 = dataclasses.replace(w, ranks=ranks2, page_idx=page_idx2, ids=ids2)
+        for a in (1, 7):
+            slora.adapter_load(dw.pool, a, int(ranks2[a]), w2.adapter_page_list(a))
+            for which in (0, 1):
+                slora.pool_write_pages(dw.pool, w2.page_idx[a][0, which], w2.weight_bits(a, 0, which), False)
+        dw.w = w2
+        got = gpu_slot(dw, 0, dw.plan(ids=ids2, seg_offsets=None))
+        assert_close(got, oracle_slot(w2, 0), "after the swap")
+        assert np.array_equal(dw.gather(7, 0, 1), w2.weight_bits(7, 0, 1))
