@@ -397,40 +397,42 @@ __device__ __forceinline__ void split_store(float f, uint16_t *frag_base, int64_
 }
 
 // ---------------------------------------------------------------------------------------
-// prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for a tile of up to 32 tokens of
-// one adapter and up to 64 of its ranks (one or two MFMA blocks of 32).
+// prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for up to 64 tokens of one adapter
+// (MB = 1 or 2 MFMA blocks of 32 rows) and up to 64 of its ranks (NB = 1 or 2 blocks).
 //
 // A classic LDS-tiled product with the second operand gathered through the page list.  H is
-// walked in chunks of 128 elements.  Per chunk the workgroup copies the 32 x-rows and the up to
-// 64 page rows (256 bytes of each) into LDS with fully coalesced 16-byte loads - 16 adjacent
-// lanes read one row's 256 bytes, so a wavefront instruction touches 8 cache lines instead of
-// the 32 a load in MFMA operand layout would - through a register ring that keeps three chunks
-// in flight per workgroup.  LDS rows are padded by 16 bytes; the four wavefronts take two of
-// the chunk's eight 16-element k-steps each, read their operands in MFMA layout with 16-byte
-// LDS loads and accumulate full 32 x 64 partial tiles, which are summed through LDS in a fixed
-// order at the end and written once (no atomics).  Token rows beyond the tile and ranks
-// beyond the adapter's are read from a valid row instead; their results are not stored, or
-// stored as zero (ranks up to the next multiple of 32, so the expand can read whole blocks).
+// walked in chunks of 128 elements.  Per chunk the workgroup copies the x rows and the page
+// rows (256 bytes of each) into LDS with fully coalesced 16-byte loads - 16 adjacent lanes
+// read one row's 256 bytes, so a wavefront instruction touches 8 cache lines instead of the 32
+// a load in MFMA operand layout would - through a register ring that keeps three chunks in
+// flight per workgroup.  LDS rows are padded by 16 bytes; the four wavefronts take two of the
+// chunk's eight 16-element k-steps each, read their operands in MFMA layout with 16-byte LDS
+// loads and accumulate full partial tiles, which are summed through LDS in a fixed order at
+// the end and written once (no atomics) as operand fragments of the expand.  Token rows beyond
+// the item and ranks beyond the adapter's are read from a valid row instead; their results are
+// not stored, or stored as zero (ranks up to the next multiple of 32, so the expand can read
+// whole blocks).  Two token blocks per item halve the number of times the pages are read.
 // ---------------------------------------------------------------------------------------
 constexpr int kMfmaThreads = 256;
 constexpr int kMfmaBlocks = kMfmaRanks / 32;     // 32-rank MFMA blocks per shrink item
 constexpr int kChunkH = 128;                     // elements of H per chunk
 constexpr int kChunkBytes = kChunkH * 2;         // bytes of one row per chunk
 constexpr int kLdsRow = kChunkBytes + 16;        // padded LDS row
-constexpr int kTileRows = 32 + kMfmaRanks;       // x rows, then page rows
+constexpr int kTileRows = 32 * kMfmaShrinkTiles + kMfmaRanks; // x rows, then page rows
 constexpr int kRing = 3;                         // chunks in flight
 constexpr int kRowsPerPass = kMfmaThreads / 16;  // rows covered by one load per thread
-constexpr int kLoadsX = 32 / kRowsPerPass;       // x rows copied per thread (2)
 
-template <int DT, int NB>
+template <int DT, int NB, int MB>
 __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *__restrict__ pa,
                                                  const unsigned char *__restrict__ x,
                                                  const uint16_t *__restrict__ pool,
                                                  const int32_t *__restrict__ tok_idx, int H, int v_stride,
                                                  uint16_t *__restrict__ vfrag, unsigned char *lds)
 {
+    constexpr int kLoadsX = MB * 32 / kRowsPerPass; // x rows copied per thread (2 or 4)
     constexpr int kLoadsP = NB * 32 / kRowsPerPass; // page rows copied per thread (2 or 4)
     constexpr int kLoads = kLoadsX + kLoadsP;
+    constexpr int kRows = 32 * (MB + NB);           // LDS rows of one buffer
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -439,7 +441,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
     const int j0 = it.a, nj = it.b;
     const int64_t row_bytes = (int64_t)H * 2;
 
-    // ---- copy duty of this thread: byte column cb of LDS rows r16 + 16*i (x rows 0..31, then pages)
+    // ---- copy duty of this thread: byte column cb of LDS rows r16 + 16*i (x rows, then pages)
     const int r16 = tid >> 4;
     const int cb = (tid & 15) * 16;
     const unsigned char *src[kLoads];
@@ -465,29 +467,36 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
         for (int i = 0; i < kLoads; ++i) r.w[i] = *reinterpret_cast<const u32x4 *>(src[i] + off);
     };
     auto stash = [&](int c, const Regs &r) { // registers -> LDS buffer c & 1; bytes past the row become zero
-        unsigned char *buf = lds + (c & 1) * (kTileRows * kLdsRow);
+        unsigned char *buf = lds + (c & 1) * (kRows * kLdsRow);
         const bool ok = (int64_t)c * kChunkBytes + cb < row_bytes;
         const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
             *reinterpret_cast<u32x4 *>(buf + (r16 + kRowsPerPass * i) * kLdsRow + cb) = ok ? r.w[i] : zero;
     };
-    f32x16 acc[NB];
+    f32x16 acc[MB][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
     auto compute = [&](int c) { // this wavefront's two k-steps of chunk c
-        const unsigned char *buf = lds + (c & 1) * (kTileRows * kLdsRow);
+        const unsigned char *buf = lds + (c & 1) * (kRows * kLdsRow);
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const int kb = (2 * wave + k) * 32 + q * 16; // byte offset of this lane's 8 k-values in the row
-            const u32x4 xa = *reinterpret_cast<const u32x4 *>(buf + row * kLdsRow + kb);
+            u32x4 xa[MB], pb[NB];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const u32x4 pb = *reinterpret_cast<const u32x4 *>(buf + (32 + nb * 32 + row) * kLdsRow + kb);
-                acc[nb] = mfma32<DT>(xa, pb, acc[nb]);
-            }
+            for (int mb = 0; mb < MB; ++mb)
+                xa[mb] = *reinterpret_cast<const u32x4 *>(buf + (mb * 32 + row) * kLdsRow + kb);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                pb[nb] = *reinterpret_cast<const u32x4 *>(buf + (32 * MB + nb * 32 + row) * kLdsRow + kb);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32<DT>(xa[mb], pb[nb], acc[mb][nb]);
         }
     };
 
@@ -510,34 +519,37 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
     __syncthreads();
 
     float(*red)[16][kWave] = reinterpret_cast<float(*)[16][kWave]>(lds);
+    constexpr int NP = VPieces<DT>::N;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[nb][e];
-        __syncthreads();
-        for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
-            const int vv = e >> 6, l = e & 63;
-            const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
-            const int i = mfma_row(vv, l);
-            const int jn = nb * 32 + (l & 31);
-            const int j = j0 + jn; // rank; ranks past the adapter's own are stored as zero
-            constexpr int NP = VPieces<DT>::N;
-            uint16_t *dst = vfrag + vfrag_index(it.tile, j >> 4, 0, v_stride >> 4, NP) +
-                            (i + 32 * ((j & 15) >> 3)) * 8 + (j & 7);
-            if (i < it.ntok) split_store<DT>(jn < nj ? s : 0.f, dst, kWave * 8);
+        for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[mb][nb][e];
+            __syncthreads();
+            for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
+                const int vv = e >> 6, l = e & 63;
+                const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
+                const int i = mfma_row(vv, l);   // token row inside v tile it.tile + mb
+                const int jn = nb * 32 + (l & 31);
+                const int j = j0 + jn;           // rank; ranks past the adapter's own are stored as zero
+                uint16_t *dst = vfrag + vfrag_index(it.tile + mb, j >> 4, 0, v_stride >> 4, NP) +
+                                (i + 32 * ((j & 15) >> 3)) * 8 + (j & 7);
+                if (mb * 32 + i < it.ntok) split_store<DT>(jn < nj ? s : 0.f, dst, kWave * 8);
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
 }
 
 template <int DT>
-__global__ __launch_bounds__(kMfmaThreads, 3) void shrink_mfma_kernel(const Item *__restrict__ items,
+__global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const Item *__restrict__ items,
                                                                        const int32_t *__restrict__ arena,
                                                                        const uint16_t *__restrict__ pool,
                                                                        const int32_t *__restrict__ tok_idx, int H,
                                                                        int v_stride, MultiArgs args)
 {
-    static_assert(kMfmaBlocks == 2 && kLoadsX == 2, "tile shape and thread mapping differ");
+    static_assert(kMfmaBlocks == 2 && kMfmaShrinkTiles == 2, "tile shapes of the scheduler and the kernel differ");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kTileRows * kLdsRow];
     static_assert(sizeof(lds) >= 4 * 16 * kWave * sizeof(float), "reduction buffer must fit");
     const int cs = mfma_slot_of(blockIdx.x, args.n);
@@ -546,10 +558,17 @@ __global__ __launch_bounds__(kMfmaThreads, 3) void shrink_mfma_kernel(const Item
     const unsigned char *x = static_cast<const unsigned char *>(args.x[cs]);
     const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a;
     uint16_t *vfrag = reinterpret_cast<uint16_t *>(args.v[cs] + args.vfrag_off);
-    if (it.b <= 32)
-        shrink_mfma_tile<DT, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
-    else
-        shrink_mfma_tile<DT, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+    if (it.ntok <= 32) {
+        if (it.b <= 32)
+            shrink_mfma_tile<DT, 1, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+        else
+            shrink_mfma_tile<DT, 2, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+    } else {
+        if (it.b <= 32)
+            shrink_mfma_tile<DT, 1, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+        else
+            shrink_mfma_tile<DT, 2, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

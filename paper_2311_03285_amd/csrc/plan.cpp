@@ -159,16 +159,24 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
             const int32_t off = (int32_t)g.arena_off;
             if ((int64_t)n >= min_tokens) {
                 plan->n_groups_mfma++;
-                static_assert(kMfmaTok == kMfmaExpandTok, "shrink and expand share the v tiles");
-                for (int32_t p = 0; p < n; p += kMfmaTok) {
-                    const int32_t nt = std::min(kMfmaTok, n - p);
-                    const int32_t tile = plan->n_mfma_tiles++;
+                // v tiles of 32 tokens, numbered in order; an expand item covers one tile, a shrink
+                // item kMfmaShrinkTiles consecutive ones (its pages are then read once for them all)
+                const int32_t tile0 = plan->n_mfma_tiles;
+                const int32_t n_tiles = (n + kMfmaTok - 1) / kMfmaTok;
+                plan->n_mfma_tiles += n_tiles;
+                for (int32_t t = 0; t < n_tiles; t += kMfmaShrinkTiles) {
+                    const int32_t p = t * kMfmaTok;
+                    const int32_t nt = std::min(kMfmaShrinkTiles * kMfmaTok, n - p);
                     for (int32_t j = 0; j < g.rank; j += kMfmaRanks)
                         plan->ms_items.push_back(
-                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, tile, 0});
+                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, tile0 + t, 0});
+                }
+                for (int32_t t = 0; t < n_tiles; ++t) {
+                    const int32_t p = t * kMfmaTok;
+                    const int32_t nt = std::min(kMfmaTok, n - p);
                     for (int32_t c = 0; c < H; c += kMfmaExpandCols)
                         plan->me_items.push_back(
-                            Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, tile, 0});
+                            Item{off, g.rank, c, std::min(kMfmaExpandCols, H - c), pos_base + p, nt, tile0 + t, 0});
                 }
             } else {
                 plan->n_groups_vec++;

@@ -52,9 +52,9 @@ constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows stage
 constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandColsMax = 3072; // most columns per vector-expand item (a multiple of 512, <= 4096)
-constexpr int kMfmaTok = 32;      // tokens per MFMA-shrink item (one 32-row MFMA block)
+constexpr int kMfmaTok = 32;      // tokens per v tile = per MFMA-expand item (one 32-row MFMA block)
+constexpr int kMfmaShrinkTiles = 2; // v tiles (32 tokens each) per MFMA-shrink item
 constexpr int kMfmaRanks = 64;    // ranks per MFMA-shrink item (two 32-column MFMA blocks)
-constexpr int kMfmaExpandTok = 32;   // tokens per MFMA-expand item (one 32-row MFMA block)
 constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item (4 wavefronts x 64)
 constexpr int kXcds = 8;         // accelerator dies (each with its own L2); MFMA lists are padded to this
 constexpr int kRankPad = 32;      // v rows are zero-padded to a multiple of this many ranks

@@ -124,7 +124,7 @@ def test_scheduler_groups_buckets_and_routes():
     # vector path, 4 pages per shrink item: adapter 1 (2 tokens, r=64): 16; adapter 2 (r=16): 4; adapter 0 (r=8): 2
     assert info["vec_shrink_items"] == 16 + 4 + 2
     assert info["vec_expand_items"] == 3 * (1024 // 512)
-    assert info["mfma_shrink_items"] == 2             # 40 tokens in tiles of 32
+    assert info["mfma_shrink_items"] == 1             # 40 tokens: one item of two 32-token tiles
     assert info["mfma_expand_items"] == 2 * (1024 // 256)    # 40 tokens in tiles of 32
     slora.plan_destroy(plan)
     slora.set_option(p, "mfma_min_tokens", 1 << 40)
@@ -135,7 +135,7 @@ def test_scheduler_groups_buckets_and_routes():
     slora.set_option(p, "xcd_group", 1)
     plan = slora.batch_plan(p, ids, seg)
     grouped = slora.plan_info(plan)
-    assert grouped["mfma_shrink_items"] == 2 and grouped["mfma_expand_items"] == 2 * (1024 // 256)
+    assert grouped["mfma_shrink_items"] == 1 and grouped["mfma_expand_items"] == 2 * (1024 // 256)
     slora.plan_destroy(plan)
     assert code(slora.set_option, p, "nope", 1) == slora.EINVAL
     assert code(slora.set_option, p, "mfma_min_tokens", 0) == slora.EINVAL
