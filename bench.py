@@ -35,38 +35,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
-    ap.add_argument("--law", default="power", choices=["power", "zipf"])
-    ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
-    ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="core-seconds of oracle work to time")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
-              "run it with --gpus 1", file=sys.stderr)
-        return 2
-
+def measure(args, workload: int, no_cpu: bool) -> dict:
+    """Time one workload; returns the JSON object of its bench line."""
     import torch
     from paper_2311_03285_amd import slora, synth
     from paper_2311_03285_amd.harness import DeviceWorkload, bits_to_device
 
     if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
+        raise RuntimeError("no GPU visible")
     slora.lib()                                   # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
     t_setup = time.time()
     R = max(1, args.batches)
-    wls = [synth.config(args.workload, batch=b, law=args.law) for b in range(R)]
+    wls = [synth.config(workload, batch=b, law=args.law) for b in range(R)]
     w0 = wls[0]
     n_slots = w0.n_slots
     # the pool: every adapter loaded at its scattered pages; seeded weights for the adapters of
@@ -178,7 +161,7 @@ def main() -> int:
 
     # ---- check the timed path against the oracle, and time the oracle as it stands -------------
     cpu = None
-    if not args.no_cpu:
+    if not no_cpu:
         from oracle import c_oracle
         w = w0
         real_slots = dw.real_slots
@@ -196,9 +179,7 @@ def main() -> int:
             rel = max(rel, float(np.linalg.norm(got - ref) / np.linalg.norm(ref)))
             mx = max(mx, float(np.abs(got - ref).max()))
         if not (rel <= 1e-3 and mx <= 1e-2):
-            print(f"bench.py: GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})",
-                  file=sys.stderr)
-            return 1
+            raise RuntimeError(f"GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})")
         # timing: whole passes (all tokens of batch 0 x the seeded slots) until ~cpu_seconds of
         # summed core time have been spent
         passes, t_cpu = 0, 0.0
@@ -234,6 +215,40 @@ def main() -> int:
         "roofline": roofline, "cpu_baseline": cpu,
     }
     dw.close()
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--law", default="power", choices=["power", "zipf"])
+    ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
+    ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="core-seconds of oracle work to time")
+    ap.add_argument("--also", default="2,3", help="workloads whose summary is nested under 'also' when the "
+                    "primary one is config 4 (comma list, 'none' to skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    try:
+        out = measure(args, args.workload, args.no_cpu)
+        if args.workload == 4 and args.also != "none":
+            keep = ("value", "unit", "ms_per_step", "hbm_gbps", "hbm_frac", "mfma_util", "config", "roofline")
+            out["also"] = []
+            for n in (int(v) for v in args.also.split(",")):
+                o = measure(args, n, True)
+                out["also"].append({k: o[k] for k in keep})
+    except RuntimeError as e:
+        print(f"bench.py: {e}", file=sys.stderr)
+        return 1
     print(json.dumps(out), flush=True)
     return 0
 
