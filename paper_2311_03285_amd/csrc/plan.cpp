@@ -128,8 +128,6 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         plan->max_shrink_tok = 0;
         int32_t max_rank = 0;
         const int32_t H = pool->H;
-        // vector-expand items: long runs of columns (several KiB of every B row are then read at
-        // once), halved while a launch would have fewer workgroups than the GPU has CUs
         // The MFMA kernels pay off when adapters have many tokens AND there are enough 32-token
         // tiles to fill the GPU: a handful of tiles is a few long, latency-bound workgroups, and
         // such groups are faster on the vector path (their pages are re-read from L2).
@@ -142,6 +140,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         int32_t n_vec_groups = 0;
         for (int32_t gi : order)
             if ((int64_t)groups[(size_t)gi].toks.size() < min_tokens) n_vec_groups++;
+        // vector-expand items: long runs of columns, halved while a launch would have fewer
+        // workgroups than the GPU has CUs
         int32_t chunks = (H + kExpandColsMax - 1) / kExpandColsMax;
         auto cols_of = [&](int32_t c) { return ((H + c - 1) / c + 511) / 512 * 512; };
         while ((int64_t)n_vec_groups * chunks < 256 && cols_of(chunks) > 512) chunks *= 2;

@@ -37,7 +37,7 @@ struct Item {
 };
 static_assert(sizeof(Item) == 32, "Item must stay 32 bytes");
 
-// Per-launch arguments for up to SLORA_MAX_MULTI slots handled by one grid (blockIdx.y).
+// Per-launch arguments for up to SLORA_MAX_MULTI slots handled by one grid.
 struct MultiArgs {
     const void *x[SLORA_MAX_MULTI];
     float *y[SLORA_MAX_MULTI];
