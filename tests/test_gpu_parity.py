@@ -237,3 +237,38 @@ def test_unload_and_reload_reuses_pages_and_table_slots():
         got = gpu_slot(dw, 0, dw.plan(ids=ids2, seg_offsets=None))
         assert_close(got, oracle_slot(w2, 0), "after the swap")
         assert np.array_equal(dw.gather(7, 0, 1), w2.weight_bits(7, 0, 1))
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_apply_can_be_captured_in_a_hip_graph():
+    """A serving loop replays the decode step as a HIP graph: once the plan's scratch exists, an
+    apply makes no allocation, copy or synchronisation, only kernel launches on the caller's
+    stream.  Every replay must reproduce the eager result bit for bit (y is reset in between by
+    eager work of the program itself)."""
+    w = ragged_workload(308, synth.F16, H=1024, T=48)
+    with DeviceWorkload(w, real_adapters="all") as dw:
+        plan = dw.plan()
+        x = [dw.x_dev(0), dw.x_dev(1)]
+        y0 = [dw.y_dev(0), dw.y_dev(1)]
+        y = [t.clone() for t in y0]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):           # eager warm-up on the capture stream: sizes the scratch
+            slora.lora_apply_multi(plan, [0, 1], [t.data_ptr() for t in x], [t.data_ptr() for t in y],
+                                   torch.cuda.current_stream())
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        eager = [t.cpu().numpy() for t in y]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            slora.lora_apply_multi(plan, [0, 1], [t.data_ptr() for t in x], [t.data_ptr() for t in y],
+                                   torch.cuda.current_stream())
+        for rep in range(4):
+            for k in range(2):
+                y[k].copy_(y0[k])               # eager work between the replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for k in range(2):
+                assert np.array_equal(y[k].cpu().numpy(), eager[k]), (rep, k)
+        assert_close(eager[0], oracle_slot(w, 0), "graph slot 0")
