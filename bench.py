@@ -98,12 +98,33 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     for i in range(args.warmup):
         step(i % R)
     torch.cuda.synchronize()
+    graph = None
+    if args.graph:
+        # one HIP graph holding a full rotation of R steps (apply makes no allocation once the
+        # plans' scratch exists); K is rounded down to a multiple of R
+        graph = torch.cuda.CUDAGraph()
+        real_stream = stream
+        with torch.cuda.graph(graph, stream=real_stream):
+            stream = torch.cuda.current_stream()
+            for b in range(R):
+                step(b)
+        stream = real_stream
+        graph.replay()
+        torch.cuda.synchronize()
+        args.steps = max(R, args.steps // R * R)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    e0.record(stream)
-    for i in range(args.steps):
-        step(i % R)
-    e1.record(stream)
+    if graph is None:
+        e0.record(stream)
+        for i in range(args.steps):
+            step(i % R)
+        e1.record(stream)
+    else:
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for i in range(args.steps // R):
+                graph.replay()
+            e1.record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ev_ms = e0.elapsed_time(e1)
@@ -205,7 +226,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "config": {"workload": w0.name, "H": w0.H, "storage": "fp16" if w0.dtype == 0 else "bf16",
                    "adapters": w0.n_adapters, "tokens_per_step": tok_per_step, "slots": n_slots,
                    "pool_pages": w0.n_pages, "popularity": args.law, "rotating_batches": R,
-                   "launch_mode": args.mode,
+                   "launch_mode": args.mode + ("+hipgraph" if args.graph else ""),
                    "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
         "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
         "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
@@ -228,6 +249,7 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--graph", action="store_true", help="replay the steps as one HIP graph per rotation")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="core-seconds of oracle work to time")
     ap.add_argument("--also", default="2,3", help="workloads whose summary is nested under 'also' when the "
