@@ -196,13 +196,23 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
 // wave-uniform and comes in through scalar loads); then one read-modify-write of y per token,
 // whose loads are issued before the row loop when there are at most two tokens.
 // ---------------------------------------------------------------------------------------
-template <int DT, int TOK, int U, bool PREFETCH_Y>
+//
+// SPLIT (small batches, where a launch has fewer workgroups than the GPU can hold): the four
+// wavefronts of a workgroup own the SAME 512 columns and take every fourth block of ranks, which
+// cuts the chain of dependent round trips of a high-rank item by four; their partial sums meet
+// in LDS (fixed order) and wavefront 0 does the read-modify-write of y.
+constexpr int kSplitWaves = 4;
+
+template <int DT, int TOK, int U, bool PREFETCH_Y, bool SPLIT>
 __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *__restrict__ pb,
                                                 const uint16_t *__restrict__ pool,
                                                 const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                float *__restrict__ y, const float *__restrict__ v, int col, bool live)
+                                                float *__restrict__ y, const float *__restrict__ v, int col, bool live,
+                                                float *red)
 {
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = SPLIT ? (int)(threadIdx.x / kWave) : 0;
+    constexpr int kStep = SPLIT ? kSplitWaves : 1;
     const float *vrow = v + (int64_t)it.pos0 * v_stride;
     float acc[TOK][8];
 #pragma unroll
@@ -215,7 +225,7 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
 #pragma unroll
     for (int t = 0; t < TOK; ++t) {
         yp[t] = y + (int64_t)tok_idx[it.pos0 + (t < it.ntok ? t : 0)] * H + col;
-        if (PREFETCH_Y && t < it.ntok && live) {
+        if (PREFETCH_Y && t < it.ntok && live && wave == 0) {
             y0[t] = *reinterpret_cast<const f32x4 *>(yp[t]);
             y1[t] = *reinterpret_cast<const f32x4 *>(yp[t] + 4);
         }
@@ -265,10 +275,28 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
         };
 
         u32x4 w[U];
-        for (int b = 0; b < nb; ++b) {
+        for (int b = wave; b < nb; b += kStep) {
             load_block(b, w);
             consume(b, w);
         }
+    }
+
+    if constexpr (SPLIT) {
+        // red[wave - 1][t][e][lane]; every wavefront of the workgroup reaches both barriers
+        if (wave > 0) {
+#pragma unroll
+            for (int t = 0; t < TOK; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) red[(((wave - 1) * TOK + t) * 8 + e) * kWave + lane] = acc[t][e];
+        }
+        __syncthreads();
+        if (wave > 0) return;
+#pragma unroll
+        for (int k = 0; k < kSplitWaves - 1; ++k)
+#pragma unroll
+            for (int t = 0; t < TOK; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[t][e] += red[((k * TOK + t) * 8 + e) * kWave + lane];
     }
 
     if (!live) return;
@@ -315,11 +343,32 @@ __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict_
     const bool live = col < col_end;
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
-        expand_vec_body<DT, 1, 16, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, 1, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else if (it.ntok == 2)
-        expand_vec_body<DT, 2, 16, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, 2, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else
-        expand_vec_body<DT, kExpandTok, 8, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live);
+        expand_vec_body<DT, kExpandTok, 8, false, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kSplitWaves *kWave) void expand_vec_split_kernel(const Item *__restrict__ items,
+                                                                              const int32_t *__restrict__ arena,
+                                                                              const uint16_t *__restrict__ pool,
+                                                                              const int32_t *__restrict__ tok_idx,
+                                                                              int H, int v_stride, MultiArgs args)
+{
+    __shared__ float red[(kSplitWaves - 1) * kExpandTok * 8 * kWave];
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
+    const int col = it.a + (int)(threadIdx.x & (kWave - 1)) * 8; // all four wavefronts: the same 512 columns
+    const bool live = col < it.a + it.b;
+    const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
+    if (it.ntok == 1)
+        expand_vec_body<DT, 1, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
+    else if (it.ntok == 2)
+        expand_vec_body<DT, 2, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
+    else
+        expand_vec_body<DT, kExpandTok, 8, false, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
 }
 
 
@@ -779,7 +828,14 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     hipStream_t st = (hipStream_t)stream;
     if (!plan->ve_items.empty()) {
         const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
-        if (pool->dtype == SLORA_F16)
+        if (plan->expand_split) {
+            if (pool->dtype == SLORA_F16)
+                hipLaunchKernelGGL(expand_vec_split_kernel<SLORA_F16>, grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
+                                   pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+            else
+                hipLaunchKernelGGL(expand_vec_split_kernel<SLORA_BF16>, grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
+                                   pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        } else if (pool->dtype == SLORA_F16)
             hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
                                plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         else

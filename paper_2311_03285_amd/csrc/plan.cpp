@@ -145,7 +145,9 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         int32_t chunks = (H + kExpandColsMax - 1) / kExpandColsMax;
         auto cols_of = [&](int32_t c) { return ((H + c - 1) / c + 511) / 512 * 512; };
         while ((int64_t)n_vec_groups * chunks < 256 && cols_of(chunks) > 512) chunks *= 2;
-        const int32_t ecols = cols_of(chunks);
+        int32_t ecols = cols_of(chunks);
+        // still short of workgroups at the smallest items: split the ranks over the wavefronts
+        plan->expand_split = ecols == 512 && (int64_t)n_vec_groups * chunks < 512;
         // the vector shrink stages its tokens' x rows in LDS: at most 64 KiB of them per item
         const int32_t shrink_tok = std::max(1, std::min(kShrinkTok, 65536 / (H * 2)));
         plan->expand_threads = ecols / 8;

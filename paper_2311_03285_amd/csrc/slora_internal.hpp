@@ -105,6 +105,7 @@ struct slora_plan {
     int32_t max_shrink_tok = 0;
     int32_t n_mfma_tiles = 0;
     int32_t expand_threads = 64; // workgroup size of the vector expand (columns per item / 8)
+    int32_t expand_split = 0;    // small batch: 512-column items, ranks split over four wavefronts
     int64_t sum_rank = 0;
     int32_t n_groups = 0, n_groups_vec = 0, n_groups_mfma = 0;
 
