@@ -114,15 +114,23 @@ def test_mfma_multi_slot_matches_single_slot():
 
 # ------------------------------------------------------------------ full-size configurations
 def _full_config(n, slots, law="power"):
+    """Full-size configuration in the launch shape the bench times: all checked slots in one
+    multi-slot call (one launch pair), each slot against the oracle."""
     w = synth.config(n, law=law)
     with DeviceWorkload(w, real_adapters="used", slots=slots) as dw:
         plan = dw.plan()
         info = slora.plan_info(plan)
-        for slot in slots:
-            got = gpu_slot(dw, slot, plan)
+        xs = [dw.x_dev(s) for s in slots]
+        ys = [dw.y_dev(s) for s in slots]
+        slora.lora_apply_multi(plan, slots, [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+        torch.cuda.synchronize()
+        for k, slot in enumerate(slots):
+            got = ys[k].cpu().numpy()
             ref = oracle_slot(w, slot)
             rel, mx = assert_close(got, ref, f"cfg{n} slot {slot}")
             assert rel <= 5e-6, rel
+            if k == 0:      # the single-slot call gives the same bits
+                assert np.array_equal(got, gpu_slot(dw, slot, plan))
         # one adapter's pages, gathered back bit for bit from the scattered pool
         a = int(w.used_adapters()[0])
         assert np.array_equal(dw.gather(a, slots[0], 1), w.weight_bits(a, slots[0], 1))
