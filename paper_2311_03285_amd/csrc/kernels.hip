@@ -553,7 +553,12 @@ __device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *
     // and chunk c+kRing is requested (chunks past the end re-read the last one and are dropped)
     Regs ring[kRing];
 #pragma unroll
-    for (int d = 0; d < kRing; ++d) load(d, ring[d]);
+    for (int d = 0; d < kRing; ++d) {
+        load(d, ring[d]);
+        // keep the three chunks' loads in issue order: the wait before a chunk is copied to LDS
+        // then counts only the loads of the two younger chunks as outstanding
+        __builtin_amdgcn_sched_barrier(0);
+    }
     const int n_rounds = (n_chunks + kRing - 1) / kRing;
     for (int rd = 0; rd < n_rounds; ++rd) {
 #pragma unroll
