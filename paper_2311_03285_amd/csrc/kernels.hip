@@ -673,6 +673,21 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
     const int n_kk = v_stride >> 4;
     const u32x4 *vfrag = reinterpret_cast<const u32x4 *>(args.v[cs] + args.vfrag_off) + lane;
 
+    const int cg = lane & 7;   // column group (8 columns) this lane copies
+    const int kp = lane >> 3;  // rank pair this lane copies
+    const int col8 = min(colw + 8 * cg, col_end - 8);
+    // page numbers of the four B rows this lane copies per stage, fetched one stage ahead
+    int pg[4];
+    auto load_pg = [&](int k0) {
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int ka = k0 + 16 * rd + 2 * kp;
+            pg[2 * rd] = pbl[min(ka, it.rank - 1)];
+            pg[2 * rd + 1] = pbl[min(ka + 1, it.rank - 1)];
+        }
+    };
+    load_pg(0);
+
     // accumulators start as the y tile (rows / columns outside the tile read a valid element)
     f32x16 acc[2];
     int ccol[2];
@@ -686,21 +701,15 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
         for (int nb = 0; nb < 2; ++nb) acc[nb][vv] = y[base + ccol[nb]];
     }
 
-    const int cg = lane & 7;   // column group (8 columns) this lane copies
-    const int kp = lane >> 3;  // rank pair this lane copies
-    const int col8 = min(colw + 8 * cg, col_end - 8);
-
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
         // ---- operands of this stage: two B rows per lane and round, V for both k-steps
         u32x4 wa[2], wb[2];
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
-            const int ka = k0 + 16 * rd + 2 * kp;
-            const int pa_ = pbl[min(ka, it.rank - 1)];
-            const int pb_ = pbl[min(ka + 1, it.rank - 1)];
-            wa[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pa_ * H + col8);
-            wb[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pb_ * H + col8);
+            wa[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pg[2 * rd] * H + col8);
+            wb[rd] = *reinterpret_cast<const u32x4 *>(pool + (int64_t)pg[2 * rd + 1] * H + col8);
         }
+        load_pg(k0 + 32); // clamped to the last rank past the end
         u32x4 piece[2][NP];
 #pragma unroll
         for (int s = 0; s < 2; ++s)
