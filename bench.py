@@ -76,7 +76,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     slots = list(range(n_slots))
 
     def x_of(b, s):
-        return xs[b][s % 4].data_ptr()
+        # --shared-x: the q, k and v projections of a layer (slots 4l .. 4l+2) read one buffer
+        return xs[b][3 if s % 4 == 3 else 0].data_ptr() if args.shared_x else xs[b][s % 4].data_ptr()
 
     def step(b):
         p = plans[b]
@@ -131,6 +132,10 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     ms_per_step = wall * 1e3 / args.steps
     tok_per_step = float(np.mean([w.T for w in wls]))
     bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
+    if args.shared_x:
+        # x of a layer's q, k, v counted once: two of every four slots' x reads drop out
+        x_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H * 2 for w in wls]))
+        bytes_step -= x_b * sum(1 for s in range(n_slots) if s % 4 in (1, 2))
     flops_step = float(np.mean([w.flops() for w in wls])) * n_slots
     value = tok_per_step * args.steps / wall
 
@@ -162,6 +167,10 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     ex_b = float(np.mean([w.expand_bytes() for w in wls]))
     sh_t = float(np.mean([t for t, n in sh]))
     ex_t = float(np.mean([t for t, n in ex]))
+    if args.shared_x:
+        # per slot of a launch: the x bytes of q, k, v are counted once (2 distinct buffers per 4 slots)
+        x_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H * 2 for w in wls]))
+        sh_b -= x_b / 2
     sh_gbs = float(np.mean([sh_b * n / t for t, n in sh])) / 1e9
     ex_gbs = float(np.mean([ex_b * n / t for t, n in ex])) / 1e9
     dom = "expand" if ex_t >= sh_t else "shrink"
@@ -226,7 +235,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "config": {"workload": w0.name, "H": w0.H, "storage": "fp16" if w0.dtype == 0 else "bf16",
                    "adapters": w0.n_adapters, "tokens_per_step": tok_per_step, "slots": n_slots,
                    "pool_pages": w0.n_pages, "popularity": args.law, "rotating_batches": R,
-                   "launch_mode": args.mode + ("+hipgraph" if args.graph else ""),
+                   "launch_mode": args.mode + ("+hipgraph" if args.graph else "") + ("+shared_x" if args.shared_x else ""),
                    "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
         "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
         "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
@@ -248,6 +257,8 @@ def main() -> int:
     ap.add_argument("--law", default="power", choices=["power", "zipf"])
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--shared-x", action="store_true",
+                    help="q, k, v of a layer read the same x buffer (as in a model); its bytes are counted once")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true", help="replay the steps as one HIP graph per rotation")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")

@@ -272,3 +272,27 @@ def test_apply_can_be_captured_in_a_hip_graph():
             for k in range(2):
                 assert np.array_equal(y[k].cpu().numpy(), eager[k]), (rep, k)
         assert_close(eager[0], oracle_slot(w, 0), "graph slot 0")
+
+
+def test_projections_sharing_one_x_buffer():
+    """q, k, v of a layer read the same activations: one call over three slots with the same x
+    pointer gives, per slot, the bits of that slot applied on its own (vector and MFMA paths)."""
+    w = ragged_workload(311, synth.F16, H=1024, n_slots=3, n_pages=1000)
+    for min_tok in (VEC_ONLY, 1):
+        with DeviceWorkload(w, real_adapters="all") as dw:
+            slora.set_option(dw.pool, "mfma_min_tokens", min_tok)
+            slora.set_option(dw.pool, "mfma_min_tiles", 1)
+            plan = dw.plan()
+            x = dw.x_dev(0)
+            single = []
+            for s in range(3):
+                y = dw.y_dev(s)
+                slora.lora_apply(plan, s, x.data_ptr(), y.data_ptr())
+                single.append(y)
+            ys = [dw.y_dev(s) for s in range(3)]
+            slora.lora_apply_multi(plan, [0, 1, 2], [x.data_ptr()] * 3, [t.data_ptr() for t in ys])
+            torch.cuda.synchronize()
+            for s in range(3):
+                assert np.array_equal(ys[s].cpu().numpy(), single[s].cpu().numpy())
+                # and against the oracle: slot s's weights, slot 0's activations
+                assert_close(ys[s].cpu().numpy(), oracle_slot(w, s, x_bits=w.x_bits(0)), f"shared x, slot {s}")
