@@ -31,6 +31,10 @@ def lib() -> C.CDLL:
         L.slo_lora_apply.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.slo_f64_to_16.restype = C.c_uint16
+        L.slo_f64_to_16.argtypes = [C.c_double, C.c_int]
+        L.slo_round16.restype = None
+        L.slo_round16.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         _lib = L
     return _lib
 
@@ -111,3 +115,22 @@ def lora_apply(pool: np.ndarray, dtype: int, lists: Dict[int, np.ndarray], ids: 
     if rc:
         raise MemoryError("oracle allocation failed")
     return (out, used.value) if return_threads else out
+
+
+def round16(values: np.ndarray, dtype: int) -> np.ndarray:
+    """fp64 -> bit patterns of the nearest binary16 / bfloat16 values (ties to even, one rounding)."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    out = np.empty(v.shape, dtype=np.uint16)
+    lib().slo_round16(_p(v), v.size, dtype, _p(out))
+    return out
+
+
+def lora_apply_y16(pool: np.ndarray, dtype: int, lists: Dict[int, np.ndarray], ids: np.ndarray,
+                   x_bits: np.ndarray, y_bits: np.ndarray, n_threads: int = 0):
+    """16-bit y: returns (bit patterns of the rounded result, the fp64 result before rounding).
+
+    y_bits holds y_in in the pool's storage type; its values are exact in fp32.
+    """
+    y32 = widen(y_bits, dtype).astype(np.float32)
+    exact = lora_apply(pool, dtype, lists, ids, x_bits, y32, n_threads)
+    return round16(exact, dtype), exact

@@ -204,3 +204,53 @@ int slo_lora_apply(const uint16_t *pool, int64_t n_pages, int32_t H, int dtype,
         *threads_used = used;
     return err;
 }
+
+/*
+ * 16-bit output (the variant in which y has the pool's storage type instead of fp32).
+ *
+ * The definition is unchanged - y_out = y_in + x A_i B_i (Sec. 2, Eq. 2) - and the result is
+ * then rounded ONCE, from the fp64 value, to the nearest binary16 / bfloat16 value, ties to
+ * even (IEEE 754 roundTiesToEven): gradual underflow to subnormals, overflow to infinity, NaN
+ * stays NaN.  A 16-bit y_in is exact in fp32, so the caller widens it and uses slo_lora_apply;
+ * this function is only the final rounding.
+ */
+uint16_t slo_f64_to_16(double v, int dtype)
+{
+    const int p = dtype == SLO_F16 ? 11 : 8;          /* significand bits, hidden one included */
+    const int emin = dtype == SLO_F16 ? -14 : -126;   /* exponent of the smallest normal value */
+    const int emax = dtype == SLO_F16 ? 15 : 127;     /* exponent of the largest finite value  */
+    const int fbits = p - 1;
+    const uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    const uint16_t inf = (uint16_t)(((2 * emax + 1) << fbits));   /* exponent field all ones */
+    if (isnan(v))
+        return (uint16_t)(sign | inf | (1u << (fbits - 1)));
+    double a = fabs(v);
+    if (isinf(a))
+        return (uint16_t)(sign | inf);
+    if (a == 0.0)
+        return sign;
+    int e;
+    (void)frexp(a, &e);
+    e -= 1;                              /* a = m * 2^e with 1 <= m < 2 */
+    if (e < emin)
+        e = emin;                        /* subnormal range: the spacing stops shrinking */
+    /* a in units of the last place at exponent e; nearbyint rounds ties to even in the default
+       rounding mode; the scaling by a power of two is exact */
+    double n = nearbyint(ldexp(a, fbits - e));
+    if (n >= ldexp(1.0, p)) {            /* rounded up into the next binade */
+        n = ldexp(1.0, fbits);
+        e += 1;
+    }
+    if (e > emax)
+        return (uint16_t)(sign | inf);
+    uint32_t N = (uint32_t)n;
+    if (N < (1u << fbits))               /* no hidden one: subnormal (e == emin) or zero */
+        return (uint16_t)(sign | N);
+    return (uint16_t)(sign | ((uint32_t)(e + emax) << fbits) | (N - (1u << fbits)));
+}
+
+void slo_round16(const double *v, int64_t n, int dtype, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = slo_f64_to_16(v[i], dtype);
+}

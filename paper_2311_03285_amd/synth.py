@@ -150,6 +150,10 @@ class Workload:
             return g.integers(-4, 5, size=(self.T, self.H)).astype(np.float32)
         return g.standard_normal((self.T, self.H), dtype=np.float32)
 
+    def y16_bits(self, slot: int = 0) -> np.ndarray:
+        """The same y_in as an input of the storage type (for the 16-bit-output variant)."""
+        return round_to_bits(self.y_in(slot), self.dtype)
+
     # ---- host views of the pool ------------------------------------------------------
     def adapter_page_list(self, adapter: int) -> np.ndarray:
         """Flat int32 list ordered [slot][A pages j=0..r-1][B pages j=0..r-1]."""
