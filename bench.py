@@ -68,7 +68,10 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         # one activation buffer per projection (q, k, v would share theirs in a model; separate
         # buffers keep cache hits on x from flattering the byte rate) and one y per slot
         xs.append([bits_to_device(w.x_bits(s), dev) for s in range(min(n_slots, 4))])
-        ys.append([torch.from_numpy(w.y_in(s % 4)).to(dev) for s in range(n_slots)])
+        if args.y16:    # y in the pool's 16-bit storage type
+            ys.append([bits_to_device(w.y16_bits(s % 4), dev) for s in range(n_slots)])
+        else:
+            ys.append([torch.from_numpy(w.y_in(s % 4)).to(dev) for s in range(n_slots)])
     torch.cuda.synchronize()
     info = slora.plan_info(plans[0])
     log(f"[bench] plan[0]: {info}")
@@ -79,21 +82,25 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         # --shared-x: the q, k and v projections of a layer (slots 4l .. 4l+2) read one buffer
         return xs[b][3 if s % 4 == 3 else 0].data_ptr() if args.shared_x else xs[b][s % 4].data_ptr()
 
+    apply_multi = slora.lora_apply_multi_y16 if args.y16 else slora.lora_apply_multi
+    expand = slora.lora_expand_y16 if args.y16 else slora.lora_expand
+    apply_one = lambda p, s, x, y, st: apply_multi(p, [s], [x], [y], st)
+
     def step(b):
         p = plans[b]
         if args.mode == "fused":
             for g0 in range(0, n_slots, slora.MAX_MULTI):
                 g = slots[g0:g0 + slora.MAX_MULTI]
-                slora.lora_apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
+                apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
         elif args.mode == "qkv_o":
             for l0 in range(0, n_slots, 4):
                 g = slots[l0:l0 + 3]
-                slora.lora_apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
+                apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
                 for s in slots[l0 + 3:l0 + 4]:
-                    slora.lora_apply(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
+                    apply_one(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
         else:
             for s in slots:
-                slora.lora_apply(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
+                apply_one(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
 
     # ---- timed region: K steps, inputs resident -------------------------------------------
     for i in range(args.warmup):
@@ -132,6 +139,9 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     ms_per_step = wall * 1e3 / args.steps
     tok_per_step = float(np.mean([w.T for w in wls]))
     bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
+    t_act_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H for w in wls]))
+    if args.y16:        # y read + written as 2-byte elements instead of 4-byte ones
+        bytes_step -= 2 * t_act_b * 2 * n_slots
     if args.shared_x:
         # x of a layer's q, k, v counted once: two of every four slots' x reads drop out
         x_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H * 2 for w in wls]))
@@ -153,7 +163,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                     slora.lora_shrink(plans[b], g, [x_of(b, s) for s in g], stream)
                 eb.record(stream)
                 for b in range(R):
-                    slora.lora_expand(plans[b], g, [ys[b][s].data_ptr() for s in g], stream)
+                    expand(plans[b], g, [ys[b][s].data_ptr() for s in g], stream)
                 ec.record(stream)
                 sh.append((ea, eb, len(g)))
                 ex.append((eb, ec, len(g)))
@@ -165,6 +175,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     sh, ex = stage_times(max(2, min(args.steps // R, 16)))
     sh_b = float(np.mean([w.shrink_bytes() for w in wls]))
     ex_b = float(np.mean([w.expand_bytes() for w in wls]))
+    if args.y16:
+        ex_b -= 2 * t_act_b * 2
     sh_t = float(np.mean([t for t, n in sh]))
     ex_t = float(np.mean([t for t, n in ex]))
     if args.shared_x:
@@ -235,7 +247,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "config": {"workload": w0.name, "H": w0.H, "storage": "fp16" if w0.dtype == 0 else "bf16",
                    "adapters": w0.n_adapters, "tokens_per_step": tok_per_step, "slots": n_slots,
                    "pool_pages": w0.n_pages, "popularity": args.law, "rotating_batches": R,
-                   "launch_mode": args.mode + ("+hipgraph" if args.graph else "") + ("+shared_x" if args.shared_x else ""),
+                   "launch_mode": args.mode + ("+hipgraph" if args.graph else "") + ("+shared_x" if args.shared_x else "") + ("+y16" if args.y16 else ""),
                    "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
         "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
         "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
@@ -257,6 +269,8 @@ def main() -> int:
     ap.add_argument("--law", default="power", choices=["power", "zipf"])
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--y16", action="store_true",
+                    help="y in the pool's 16-bit storage type (rounded once at the store) instead of fp32")
     ap.add_argument("--shared-x", action="store_true",
                     help="q, k, v of a layer read the same x buffer (as in a model); its bytes are counted once")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")

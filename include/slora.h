@@ -164,6 +164,21 @@ int32_t slora_lora_shrink(slora_plan *plan, int32_t n, const int32_t *slots,
 int32_t slora_lora_expand(slora_plan *plan, int32_t n, const int32_t *slots,
                           float *const *y, void *stream);
 
+/*
+ * 16-bit y.  The `add` node of Fig. 1 adds xAB onto the base model's xW; a serving stack keeps
+ * that activation in the model's 16-bit type.  These variants take y[k] as DEVICE pointers to
+ * T*H elements of the POOL'S STORAGE TYPE (binary16 or bfloat16), row-major, and compute
+ *      y[t,d] = round16( fp32(y[t,d]) + sum_j v[t,j] * B_i[j,d] )
+ * with the sum accumulated in fp32 exactly as in the fp32-y calls and ONE rounding to nearest,
+ * ties to even, at the store.  Everything else (arguments, errors, asynchrony, rows that are
+ * never touched, determinism) is as for slora_lora_apply_multi / slora_lora_expand; the shrink
+ * stage is shared (slora_lora_shrink).  This halves the y traffic that dominates prefill.
+ */
+int32_t slora_lora_apply_multi_y16(slora_plan *plan, int32_t n, const int32_t *slots,
+                                   const void *const *x, void *const *y, void *stream);
+int32_t slora_lora_expand_y16(slora_plan *plan, int32_t n, const int32_t *slots,
+                              void *const *y, void *stream);
+
 /* One-shot form: plan + apply(slot) + plan_destroy; returns after the work has completed. */
 int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
                                  const int32_t *token_adapter_ids, const int32_t *seg_offsets,

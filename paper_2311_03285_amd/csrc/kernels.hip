@@ -58,6 +58,81 @@ __device__ __forceinline__ void widen2(uint32_t u, float &lo, float &hi)
     }
 }
 
+// one fp32 value rounded to the 16-bit storage type (nearest, ties to even) and back
+template <int DT>
+__device__ __forceinline__ uint16_t narrow1(float f)
+{
+    if constexpr (DT == SLORA_F16)
+        return __builtin_bit_cast(uint16_t, (_Float16)f);
+    else
+        return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+template <int DT>
+__device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+{
+    return (uint32_t)narrow1<DT>(lo) | ((uint32_t)narrow1<DT>(hi) << 16);
+}
+template <int DT>
+__device__ __forceinline__ float widen1(uint16_t b)
+{
+    if constexpr (DT == SLORA_F16)
+        return (float)__builtin_bit_cast(_Float16, b);
+    else
+        return __uint_as_float((uint32_t)b << 16);
+}
+
+// Eight consecutive elements of a row of y: fp32 (Y16 = false) or the pool's 16-bit storage
+// type (Y16 = true; the sum is formed in fp32 and rounded once, to nearest even, on the way out).
+// `off` is an element offset and a multiple of 8, so every access is 16-byte aligned.
+template <int DT, bool Y16>
+struct Y8;
+template <int DT>
+struct Y8<DT, false> {
+    f32x4 a, b;
+    __device__ __forceinline__ void load(const void *y, int64_t off)
+    {
+        const float *p = static_cast<const float *>(y) + off;
+        a = *reinterpret_cast<const f32x4 *>(p);
+        b = *reinterpret_cast<const f32x4 *>(p + 4);
+    }
+    __device__ __forceinline__ void add_store(void *y, int64_t off, const float (&d)[8])
+    {
+        float *p = static_cast<float *>(y) + off;
+        a.x += d[0];
+        a.y += d[1];
+        a.z += d[2];
+        a.w += d[3];
+        b.x += d[4];
+        b.y += d[5];
+        b.z += d[6];
+        b.w += d[7];
+        *reinterpret_cast<f32x4 *>(p) = a;
+        *reinterpret_cast<f32x4 *>(p + 4) = b;
+    }
+};
+template <int DT>
+struct Y8<DT, true> {
+    u32x4 r;
+    __device__ __forceinline__ void load(const void *y, int64_t off)
+    {
+        r = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(y) + off);
+    }
+    __device__ __forceinline__ void add_store(void *y, int64_t off, const float (&d)[8])
+    {
+        float f[8];
+        widen2<DT>(r.x, f[0], f[1]);
+        widen2<DT>(r.y, f[2], f[3]);
+        widen2<DT>(r.z, f[4], f[5]);
+        widen2<DT>(r.w, f[6], f[7]);
+        u32x4 o;
+        o.x = narrow2<DT>(f[0] + d[0], f[1] + d[1]);
+        o.y = narrow2<DT>(f[2] + d[2], f[3] + d[3]);
+        o.z = narrow2<DT>(f[4] + d[4], f[5] + d[5]);
+        o.w = narrow2<DT>(f[6] + d[6], f[7] + d[7]);
+        *reinterpret_cast<u32x4 *>(static_cast<uint16_t *>(y) + off) = o;
+    }
+};
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -203,11 +278,11 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
 // in LDS (fixed order) and wavefront 0 does the read-modify-write of y.
 constexpr int kSplitWaves = 4;
 
-template <int DT, int TOK, int U, bool PREFETCH_Y, bool SPLIT>
+template <int DT, bool Y16, int TOK, int U, bool PREFETCH_Y, bool SPLIT>
 __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *__restrict__ pb,
                                                 const uint16_t *__restrict__ pool,
                                                 const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                float *__restrict__ y, const float *__restrict__ v, int col, bool live,
+                                                void *__restrict__ y, const float *__restrict__ v, int col, bool live,
                                                 float *red)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -220,15 +295,12 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
 
-    f32x4 y0[TOK], y1[TOK];
-    float *yp[TOK];
+    Y8<DT, Y16> yv[TOK];
+    int64_t yoff[TOK];
 #pragma unroll
     for (int t = 0; t < TOK; ++t) {
-        yp[t] = y + (int64_t)tok_idx[it.pos0 + (t < it.ntok ? t : 0)] * H + col;
-        if (PREFETCH_Y && t < it.ntok && live && wave == 0) {
-            y0[t] = *reinterpret_cast<const f32x4 *>(yp[t]);
-            y1[t] = *reinterpret_cast<const f32x4 *>(yp[t] + 4);
-        }
+        yoff[t] = (int64_t)tok_idx[it.pos0 + (t < it.ntok ? t : 0)] * H + col;
+        if (PREFETCH_Y && t < it.ntok && live && wave == 0) yv[t].load(y, yoff[t]);
     }
 
     const int col_ld = live ? col : it.a;
@@ -303,29 +375,13 @@ __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *_
 #pragma unroll
     for (int t = 0; t < TOK; ++t) {
         if (t < it.ntok) {
-            f32x4 a, b;
-            if (PREFETCH_Y) {
-                a = y0[t];
-                b = y1[t];
-            } else {
-                a = *reinterpret_cast<const f32x4 *>(yp[t]);
-                b = *reinterpret_cast<const f32x4 *>(yp[t] + 4);
-            }
-            a.x += acc[t][0];
-            a.y += acc[t][1];
-            a.z += acc[t][2];
-            a.w += acc[t][3];
-            b.x += acc[t][4];
-            b.y += acc[t][5];
-            b.z += acc[t][6];
-            b.w += acc[t][7];
-            *reinterpret_cast<f32x4 *>(yp[t]) = a;
-            *reinterpret_cast<f32x4 *>(yp[t] + 4) = b;
+            if (!PREFETCH_Y) yv[t].load(y, yoff[t]);
+            yv[t].add_store(y, yoff[t], acc[t]);
         }
     }
 }
 
-template <int DT>
+template <int DT, bool Y16>
 __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict__ items,
                                                           const int32_t *__restrict__ arena,
                                                           const uint16_t *__restrict__ pool,
@@ -343,14 +399,14 @@ __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict_
     const bool live = col < col_end;
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
-        expand_vec_body<DT, 1, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+        expand_vec_body<DT, Y16, 1, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else if (it.ntok == 2)
-        expand_vec_body<DT, 2, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+        expand_vec_body<DT, Y16, 2, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else
-        expand_vec_body<DT, kExpandTok, 8, false, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+        expand_vec_body<DT, Y16, kExpandTok, 8, false, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
 }
 
-template <int DT>
+template <int DT, bool Y16>
 __global__ __launch_bounds__(kSplitWaves *kWave) void expand_vec_split_kernel(const Item *__restrict__ items,
                                                                               const int32_t *__restrict__ arena,
                                                                               const uint16_t *__restrict__ pool,
@@ -364,11 +420,11 @@ __global__ __launch_bounds__(kSplitWaves *kWave) void expand_vec_split_kernel(co
     const bool live = col < it.a + it.b;
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
-        expand_vec_body<DT, 1, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
+        expand_vec_body<DT, Y16, 1, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
     else if (it.ntok == 2)
-        expand_vec_body<DT, 2, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
+        expand_vec_body<DT, Y16, 2, 16, true, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
     else
-        expand_vec_body<DT, kExpandTok, 8, false, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
+        expand_vec_body<DT, Y16, kExpandTok, 8, false, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
 }
 
 
@@ -647,9 +703,10 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const Item
 // stored.
 // ---------------------------------------------------------------------------------------
 constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
+constexpr int kYTileStride = 72; // 16-bit y tile in the same slab: elements per row, 64 + 8 pad (144 bytes)
 
-template <int DT>
-__global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *__restrict__ items,
+template <int DT, bool Y16>
+__global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item *__restrict__ items,
                                                                     const int32_t *__restrict__ arena,
                                                                     const uint16_t *__restrict__ pool,
                                                                     const int32_t *__restrict__ tok_idx, int H,
@@ -659,7 +716,8 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
     const int cs = mfma_slot_of(blockIdx.x, args.n);
     const Item it = items[mfma_item_of(blockIdx.x, args.n)];
     if (it.ntok == 0) return; // padding of a short per-XCD list
-    float *__restrict__ y = args.y[cs];
+    float *y = static_cast<float *>(args.y[cs]);       // one buffer; an instance uses one of the two views
+    uint16_t *y16 = static_cast<uint16_t *>(args.y[cs]);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int n = lane & 31;
@@ -690,15 +748,42 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
 
     // accumulators start as the y tile (rows / columns outside the tile read a valid element)
     f32x16 acc[2];
-    int ccol[2];
+    // 16-bit y: the 32 x 64 tile (4 KiB) passes through the wavefront's LDS slab, which is idle
+    // before the first and after the last stage: 16-byte accesses of whole 128-byte row pieces
+    // towards memory, 2-byte LDS accesses in accumulator layout on the other side.  Lane l moves
+    // the 8 columns of group l % 8 of rows l / 8 + 8 i.
+    uint16_t *ytile = reinterpret_cast<uint16_t *>(slab);
+    int64_t yrow16[4];
+    if constexpr (Y16) {
+        static_assert(32 * kYTileStride * 2 <= 64 * kSlabStride * 4, "y tile must fit into the B slab");
+        const int ycol = min(colw + 8 * (lane & 7), col_end - 8);
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) ccol[nb] = min(colw + nb * 32 + n, col_end - 1);
+        for (int i = 0; i < 4; ++i) {
+            const int r = (lane >> 3) + 8 * i;
+            yrow16[i] = (int64_t)tok_idx[it.pos0 + min(r, it.ntok - 1)] * H;
+            const u32x4 w8 = *reinterpret_cast<const u32x4 *>(y16 + yrow16[i] + ycol);
+            *reinterpret_cast<u32x4 *>(ytile + r * kYTileStride + 8 * (lane & 7)) = w8;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int vv = 0; vv < 16; ++vv) {
-        const int i = mfma_row(vv, lane);
-        const int64_t base = (int64_t)tok_idx[it.pos0 + (i < it.ntok ? i : 0)] * H;
+        for (int vv = 0; vv < 16; ++vv)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) acc[nb][vv] = y[base + ccol[nb]];
+            for (int nb = 0; nb < 2; ++nb)
+                acc[nb][vv] = widen1<DT>(ytile[mfma_row(vv, lane) * kYTileStride + nb * 32 + n]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // the stages overwrite the slab
+    } else {
+        int ccol[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) ccol[nb] = min(colw + nb * 32 + n, col_end - 1);
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+            const int i = mfma_row(vv, lane);
+            const int64_t base = (int64_t)tok_idx[it.pos0 + (i < it.ntok ? i : 0)] * H;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) acc[nb][vv] = y[base + ccol[nb]];
+        }
     }
 
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
@@ -744,15 +829,35 @@ __global__ __launch_bounds__(kMfmaThreads) void expand_mfma_kernel(const Item *_
         }
     }
 
+    if constexpr (Y16) {
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int vv = 0; vv < 16; ++vv) {
-        const int i = mfma_row(vv, lane);
-        if (i < it.ntok) {
-            const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
+        for (int vv = 0; vv < 16; ++vv)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int c = colw + nb * 32 + n;
-                if (c < col_end) y[base + c] = acc[nb][vv];
+            for (int nb = 0; nb < 2; ++nb)
+                ytile[mfma_row(vv, lane) * kYTileStride + nb * 32 + n] = narrow1<DT>(acc[nb][vv]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int ycol = colw + 8 * (lane & 7); // a multiple of 8, like col_end: a group is inside or outside
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = (lane >> 3) + 8 * i;
+            if (r < it.ntok && ycol < col_end)
+                *reinterpret_cast<u32x4 *>(y16 + yrow16[i] + ycol) =
+                    *reinterpret_cast<const u32x4 *>(ytile + r * kYTileStride + 8 * (lane & 7));
+        }
+    } else {
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+            const int i = mfma_row(vv, lane);
+            if (i < it.ntok) {
+                const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const int c = colw + nb * 32 + n;
+                    if (c < col_end) y[base + c] = acc[nb][vv];
+                }
             }
         }
     }
@@ -835,40 +940,34 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     return SLORA_OK;
 }
 
-int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream)
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16)
 {
     slora_pool *pool = plan->pool;
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
+    // (storage type, y type) -> kernel instance
+#define SLORA_PICK(KERNEL)                                                                   \
+    (pool->dtype == SLORA_F16 ? (y16 ? KERNEL<SLORA_F16, true> : KERNEL<SLORA_F16, false>)   \
+                              : (y16 ? KERNEL<SLORA_BF16, true> : KERNEL<SLORA_BF16, false>))
     if (!plan->ve_items.empty()) {
         const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
-        if (plan->expand_split) {
-            if (pool->dtype == SLORA_F16)
-                hipLaunchKernelGGL(expand_vec_split_kernel<SLORA_F16>, grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
-                                   pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
-            else
-                hipLaunchKernelGGL(expand_vec_split_kernel<SLORA_BF16>, grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
-                                   pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
-        } else if (pool->dtype == SLORA_F16)
-            hipLaunchKernelGGL(expand_vec_kernel<SLORA_F16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
-                               plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        if (plan->expand_split)
+            hipLaunchKernelGGL(SLORA_PICK(expand_vec_split_kernel), grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
+                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         else
-            hipLaunchKernelGGL(expand_vec_kernel<SLORA_BF16>, grid, dim3((unsigned)plan->expand_threads), 0, st,
+            hipLaunchKernelGGL(SLORA_PICK(expand_vec_kernel), grid, dim3((unsigned)plan->expand_threads), 0, st,
                                plan->d_ve, pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         int32_t rc = check_launch("expand_vec");
         if (rc != SLORA_OK) return rc;
     }
     if (!plan->me_items.empty()) {
         const dim3 grid((unsigned)(plan->me_items.size() * (size_t)n));
-        if (pool->dtype == SLORA_F16)
-            hipLaunchKernelGGL(expand_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
-                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
-        else
-            hipLaunchKernelGGL(expand_mfma_kernel<SLORA_BF16>, grid, dim3(kMfmaThreads), 0, st, plan->d_me,
-                               pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
+        hipLaunchKernelGGL(SLORA_PICK(expand_mfma_kernel), grid, dim3(kMfmaThreads), 0, st, plan->d_me, pool->d_arena,
+                           base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         int32_t rc = check_launch("expand_mfma");
         if (rc != SLORA_OK) return rc;
     }
+#undef SLORA_PICK
     return SLORA_OK;
 }
 

@@ -306,17 +306,26 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
     return rc;
 }
 
-int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *const *y, void *stream)
+int32_t check_y(int32_t n, void *const *y)
 {
     if (!y) return fail(SLORA_EINVAL, "y is NULL");
-    if (plan->T_act == 0) return SLORA_OK;
-    MultiArgs a{};
-    a.n = n;
     for (int32_t k = 0; k < n; ++k) {
         if (!y[k]) return fail(SLORA_EINVAL, "y[%d] is NULL", k);
         if (reinterpret_cast<uintptr_t>(y[k]) & 15) return fail(SLORA_EINVAL, "y[%d] must be 16-byte aligned", k);
         for (int32_t m = 0; m < k; ++m)
             if (y[m] == y[k]) return fail(SLORA_EINVAL, "y[%d] and y[%d] are the same buffer", m, k);
+    }
+    return SLORA_OK;
+}
+
+int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const *y, void *stream, bool y16)
+{
+    int32_t rc = check_y(n, y);
+    if (rc != SLORA_OK) return rc;
+    if (plan->T_act == 0) return SLORA_OK;
+    MultiArgs a{};
+    a.n = n;
+    for (int32_t k = 0; k < n; ++k) {
         a.y[k] = y[k];
         a.slot[k] = slots[k];
     }
@@ -326,7 +335,7 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, float *cons
     if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
     for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
     a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
-    return launch_expand(plan, n, a, stream);
+    return launch_expand(plan, n, a, stream, y16);
 }
 
 } // namespace
@@ -403,26 +412,41 @@ int32_t slora_lora_expand(slora_plan *plan, int32_t n, const int32_t *slots, flo
 {
     clear_error();
     int32_t rc = check_plan(plan, n, slots);
-    return rc != SLORA_OK ? rc : do_expand(plan, n, slots, y, stream);
+    return rc != SLORA_OK ? rc : do_expand(plan, n, slots, reinterpret_cast<void *const *>(y), stream, false);
 }
 
-int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
-                               float *const *y, void *stream)
+int32_t slora_lora_expand_y16(slora_plan *plan, int32_t n, const int32_t *slots, void *const *y, void *stream)
+{
+    clear_error();
+    int32_t rc = check_plan(plan, n, slots);
+    return rc != SLORA_OK ? rc : do_expand(plan, n, slots, y, stream, true);
+}
+
+namespace {
+int32_t apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *const *y,
+                    void *stream, bool y16)
 {
     clear_error();
     int32_t rc = check_plan(plan, n, slots);
     if (rc != SLORA_OK) return rc;
-    // validate the y side before the shrink is enqueued
-    if (!y) return fail(SLORA_EINVAL, "y is NULL");
-    for (int32_t k = 0; k < n; ++k) {
-        if (!y[k]) return fail(SLORA_EINVAL, "y[%d] is NULL", k);
-        if (reinterpret_cast<uintptr_t>(y[k]) & 15) return fail(SLORA_EINVAL, "y[%d] must be 16-byte aligned", k);
-        for (int32_t m = 0; m < k; ++m)
-            if (y[m] == y[k]) return fail(SLORA_EINVAL, "y[%d] and y[%d] are the same buffer", m, k);
-    }
+    rc = check_y(n, y); // validate the y side before the shrink is enqueued
+    if (rc != SLORA_OK) return rc;
     rc = do_shrink(plan, n, slots, x, stream);
     if (rc != SLORA_OK) return rc;
-    return do_expand(plan, n, slots, y, stream);
+    return do_expand(plan, n, slots, y, stream, y16);
+}
+} // namespace
+
+int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
+                               float *const *y, void *stream)
+{
+    return apply_multi(plan, n, slots, x, reinterpret_cast<void *const *>(y), stream, false);
+}
+
+int32_t slora_lora_apply_multi_y16(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
+                                   void *const *y, void *stream)
+{
+    return apply_multi(plan, n, slots, x, y, stream, true);
 }
 
 int32_t slora_lora_apply(slora_plan *plan, int32_t slot, const void *x, float *y, void *stream)

@@ -40,7 +40,7 @@ static_assert(sizeof(Item) == 32, "Item must stay 32 bytes");
 // Per-launch arguments for up to SLORA_MAX_MULTI slots handled by one grid.
 struct MultiArgs {
     const void *x[SLORA_MAX_MULTI];
-    float *y[SLORA_MAX_MULTI];
+    void *y[SLORA_MAX_MULTI];   // fp32 rows, or rows of the pool's storage type (16-bit y variant)
     float *v[SLORA_MAX_MULTI];
     int32_t slot[SLORA_MAX_MULTI];
     int32_t n; // slots in this launch; workgroup b handles item b / n for slot entry b % n
@@ -142,6 +142,6 @@ int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, co
                            void *stream);
 int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void *dev_out, void *stream);
 int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
-int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16);
 
 } // namespace slora

@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
             "slora_plan_info": (i32, [vp, vp, i32]),
             "slora_lora_apply": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_apply_multi": (i32, [vp, i32, vp, vp, vp, vp]),
+            "slora_lora_apply_multi_y16": (i32, [vp, i32, vp, vp, vp, vp]),
+            "slora_lora_expand_y16": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_shrink": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_expand": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_shrink_expand": (i32, [vp, i32, vp, vp, vp, i32, i32, vp, vp]),
@@ -165,6 +167,17 @@ def lora_apply(plan, slot: int, x: int, y: int, stream=None) -> None:
 def lora_apply_multi(plan, slots, xs: Sequence[int], ys: Sequence[int], stream=None) -> None:
     s = _i32(slots)
     _check(lib().slora_lora_apply_multi(plan, s.size, _ptr(s), _ptr_array(xs), _ptr_array(ys), _stream(stream)))
+
+
+def lora_apply_multi_y16(plan, slots, xs: Sequence[int], ys: Sequence[int], stream=None) -> None:
+    """As lora_apply_multi, with every y of the pool's 16-bit storage type."""
+    s = _i32(slots)
+    _check(lib().slora_lora_apply_multi_y16(plan, s.size, _ptr(s), _ptr_array(xs), _ptr_array(ys), _stream(stream)))
+
+
+def lora_expand_y16(plan, slots, ys: Sequence[int], stream=None) -> None:
+    s = _i32(slots)
+    _check(lib().slora_lora_expand_y16(plan, s.size, _ptr(s), _ptr_array(ys), _stream(stream)))
 
 
 def lora_shrink(plan, slots, xs: Sequence[int], stream=None) -> None:
