@@ -703,7 +703,23 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const Item
 // stored.
 // ---------------------------------------------------------------------------------------
 constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
-constexpr int kYTileStride = 72; // 16-bit y tile in the same slab: elements per row, 64 + 8 pad (144 bytes)
+// The y tile of a wavefront (32 rows x 64 columns) is staged in the same slab; padded rows keep the
+// 16-byte alignment and spread the accumulator-layout accesses over the banks.
+template <bool Y16>
+struct YTile;
+template <>
+struct YTile<true> {
+    using type = uint16_t;
+    static constexpr int stride = 72;                  // 144-byte rows
+    static constexpr int bytes = 32 * stride * 2;
+};
+template <>
+struct YTile<false> {
+    using type = float;
+    static constexpr int stride = 68;                  // 272-byte rows
+    static constexpr int bytes = 32 * stride * 4;
+};
+constexpr int kSlabBytes = 64 * kSlabStride * 4;
 
 template <int DT, bool Y16>
 __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item *__restrict__ items,
@@ -712,12 +728,12 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
                                                                     const int32_t *__restrict__ tok_idx, int H,
                                                                     int v_stride, MultiArgs args)
 {
-    __shared__ u32x4 slab_mem[4][64 * kSlabStride / 4];
+    constexpr int kWaveLds = YTile<Y16>::bytes > kSlabBytes ? YTile<Y16>::bytes : kSlabBytes;
+    __shared__ u32x4 slab_mem[4][kWaveLds / 16];
     const int cs = mfma_slot_of(blockIdx.x, args.n);
     const Item it = items[mfma_item_of(blockIdx.x, args.n)];
     if (it.ntok == 0) return; // padding of a short per-XCD list
-    float *y = static_cast<float *>(args.y[cs]);       // one buffer; an instance uses one of the two views
-    uint16_t *y16 = static_cast<uint16_t *>(args.y[cs]);
+    void *args_y = args.y[cs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int n = lane & 31;
@@ -748,21 +764,26 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
 
     // accumulators start as the y tile (rows / columns outside the tile read a valid element)
     f32x16 acc[2];
-    // 16-bit y: the 32 x 64 tile (4 KiB) passes through the wavefront's LDS slab, which is idle
-    // before the first and after the last stage: 16-byte accesses of whole 128-byte row pieces
-    // towards memory, 2-byte LDS accesses in accumulator layout on the other side.  Lane l moves
-    // the 8 columns of group l % 8 of rows l / 8 + 8 i.
-    uint16_t *ytile = reinterpret_cast<uint16_t *>(slab);
-    int64_t yrow16[4];
-    if constexpr (Y16) {
-        static_assert(32 * kYTileStride * 2 <= 64 * kSlabStride * 4, "y tile must fit into the B slab");
-        const int ycol = min(colw + 8 * (lane & 7), col_end - 8);
+    // The 32 x 64 tile of y passes through the wavefront's LDS slab, which is idle before the
+    // first and after the last stage: 16-byte accesses of whole row pieces (128 or 256 bytes)
+    // towards memory, single-element LDS accesses in accumulator layout on the other side.
+    // A lane moves the kYVec columns of group lane % kYLanes of rows lane / kYLanes + kYRows * i.
+    using YT = typename YTile<Y16>::type;
+    constexpr int kYVec = 16 / (int)sizeof(YT);   // elements per 16-byte access
+    constexpr int kYLanes = 64 / kYVec;           // lanes per tile row
+    constexpr int kYRows = kWave / kYLanes;       // rows per access of the wavefront
+    constexpr int kYStride = YTile<Y16>::stride;  // padded row, elements
+    YT *ytile = reinterpret_cast<YT *>(slab);
+    YT *yg = static_cast<YT *>(args_y);
+    const int ygrp = lane % kYLanes;
+    {
+        const int ycol = min(colw + kYVec * ygrp, col_end - kYVec);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (lane >> 3) + 8 * i;
-            yrow16[i] = (int64_t)tok_idx[it.pos0 + min(r, it.ntok - 1)] * H;
-            const u32x4 w8 = *reinterpret_cast<const u32x4 *>(y16 + yrow16[i] + ycol);
-            *reinterpret_cast<u32x4 *>(ytile + r * kYTileStride + 8 * (lane & 7)) = w8;
+        for (int i = 0; i < 32 / kYRows; ++i) {
+            const int r = lane / kYLanes + kYRows * i;
+            const int64_t row = (int64_t)tok_idx[it.pos0 + min(r, it.ntok - 1)] * H;
+            const u32x4 w8 = *reinterpret_cast<const u32x4 *>(yg + row + ycol);
+            *reinterpret_cast<u32x4 *>(ytile + r * kYStride + kYVec * ygrp) = w8;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -770,20 +791,14 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
 #pragma unroll
         for (int vv = 0; vv < 16; ++vv)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-                acc[nb][vv] = widen1<DT>(ytile[mfma_row(vv, lane) * kYTileStride + nb * 32 + n]);
+            for (int nb = 0; nb < 2; ++nb) {
+                const YT e = ytile[mfma_row(vv, lane) * kYStride + nb * 32 + n];
+                if constexpr (Y16)
+                    acc[nb][vv] = widen1<DT>(e);
+                else
+                    acc[nb][vv] = e;
+            }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // the stages overwrite the slab
-    } else {
-        int ccol[2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) ccol[nb] = min(colw + nb * 32 + n, col_end - 1);
-#pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-            const int i = mfma_row(vv, lane);
-            const int64_t base = (int64_t)tok_idx[it.pos0 + (i < it.ntok ? i : 0)] * H;
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) acc[nb][vv] = y[base + ccol[nb]];
-        }
     }
 
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
@@ -829,36 +844,28 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
         }
     }
 
-    if constexpr (Y16) {
-        __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv)
+    for (int vv = 0; vv < 16; ++vv)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-                ytile[mfma_row(vv, lane) * kYTileStride + nb * 32 + n] = narrow1<DT>(acc[nb][vv]);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int ycol = colw + 8 * (lane & 7); // a multiple of 8, like col_end: a group is inside or outside
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (lane >> 3) + 8 * i;
-            if (r < it.ntok && ycol < col_end)
-                *reinterpret_cast<u32x4 *>(y16 + yrow16[i] + ycol) =
-                    *reinterpret_cast<const u32x4 *>(ytile + r * kYTileStride + 8 * (lane & 7));
+        for (int nb = 0; nb < 2; ++nb) {
+            YT &e = ytile[mfma_row(vv, lane) * kYStride + nb * 32 + n];
+            if constexpr (Y16)
+                e = narrow1<DT>(acc[nb][vv]);
+            else
+                e = acc[nb][vv];
         }
-    } else {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int ycol = colw + kYVec * ygrp; // a multiple of kYVec, and col_end one of 8: a group is inside or outside
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-            const int i = mfma_row(vv, lane);
-            if (i < it.ntok) {
-                const int64_t base = (int64_t)tok_idx[it.pos0 + i] * H;
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const int c = colw + nb * 32 + n;
-                    if (c < col_end) y[base + c] = acc[nb][vv];
-                }
-            }
+    for (int i = 0; i < 32 / kYRows; ++i) {
+        const int r = lane / kYLanes + kYRows * i;
+        if (r < it.ntok && ycol < col_end) {
+            const int64_t row = (int64_t)tok_idx[it.pos0 + r] * H;
+            *reinterpret_cast<u32x4 *>(yg + row + ycol) =
+                *reinterpret_cast<const u32x4 *>(ytile + r * kYStride + kYVec * ygrp);
         }
     }
 }
