@@ -104,6 +104,37 @@ int32_t slora_adapter_load(slora_pool *pool, int32_t adapter_id, int32_t rank,
 int32_t slora_adapter_unload(slora_pool *pool, int32_t adapter_id);
 
 /*
+ * Page allocator of the unified pool (Sec. 5.1: KV cache and adapter weights draw H-vector pages
+ * from one pool; since every request is for single pages there is no fragmentation, and the
+ * two uses compete for the same free pages).  These calls let the LIBRARY choose the pages;
+ * they mix freely with the calls above that name pages explicitly.
+ *
+ * slora_pool_free_pages: number of pages owned by nobody.
+ * slora_pool_alloc_kv:   take n free pages for KV cache; their indices go to out_idx (HOST,
+ *                        n entries).  Release them with slora_pool_mark_kv(..., owned = 0).
+ * slora_adapter_alloc:   make the adapter resident on n_slots*2*rank pages of the library's
+ *                        choice; out_idx (HOST, may be NULL) receives them in the order
+ *                        [slot][A columns][B rows].  Errors as slora_adapter_load.
+ * When fewer pages are free than asked for, both return SLORA_ENOMEM and take nothing: the
+ * caller evicts an adapter or releases KV pages and tries again.
+ */
+int32_t slora_pool_free_pages(const slora_pool *pool, int64_t *out);
+int32_t slora_pool_alloc_kv(slora_pool *pool, int64_t n, int32_t *out_idx);
+int32_t slora_adapter_alloc(slora_pool *pool, int32_t adapter_id, int32_t rank, int32_t *out_idx);
+
+/*
+ * Fetch a resident adapter's weights into its pages, asynchronously on `stream` (Sec. 5.2: the
+ * adapters of waiting requests are fetched while the running batch computes, so the copy is
+ * hidden).  weights: PINNED HOST memory (hipHostMalloc; a pageable pointer is rejected with
+ * EINVAL) or DEVICE memory, 16-byte aligned, n_slots*2*rank vectors of H elements of the pool's
+ * storage type ordered [slot][A columns j][B rows j].  One kernel on `stream` reads the source
+ * in place (over the host link for pinned memory) and scatters it to the pages: no staging
+ * buffer, no synchronisation.  The source must stay valid until the stream has run the kernel;
+ * an apply that uses the adapter must be ordered after it (same stream, or an event).
+ */
+int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *weights, void *stream);
+
+/*
  * Gather one paged matrix into contiguous DEVICE memory: dev_out[j*H + h] = page j of the A
  * (which = 0) or B (which = 1) list of (adapter, slot); rank*H elements, bit-exact copies.
  */

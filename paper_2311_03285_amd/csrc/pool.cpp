@@ -72,6 +72,80 @@ int32_t slora_pool::sync_device()
     return SLORA_OK;
 }
 
+void slora_pool::set_state(int64_t page, uint8_t to)
+{
+    uint8_t &s = state[(size_t)page];
+    if (s == kFree && to != kFree) n_free--;
+    if (s != kFree && to == kFree) {
+        n_free++;
+        try {
+            released.push_back((int32_t)page);
+        } catch (const std::bad_alloc &) { /* the page stays free but is not handed out again */
+        }
+    }
+    s = to;
+}
+
+int32_t slora_pool::take(int64_t n, uint8_t as, int32_t *out)
+{
+    if (n > n_free)
+        return fail(SLORA_ENOMEM, "%lld page(s) wanted, %lld free: KV cache and adapters share the pool",
+                    (long long)n, (long long)n_free);
+    int64_t got = 0;
+    while (got < n) {
+        int64_t p = -1;
+        if (!released.empty()) {
+            p = released.back();
+            released.pop_back();
+            if (state[(size_t)p] != kFree) continue; // taken by index since it was released
+        } else {
+            while (fresh < n_pages && state[(size_t)fresh] != kFree) fresh++;
+            if (fresh >= n_pages) break; // cannot happen while n_free is right
+            p = fresh++;
+        }
+        state[(size_t)p] = as;
+        n_free--;
+        out[got++] = (int32_t)p;
+    }
+    if (got < n) { // give back what was taken; the count was wrong (a page could not be recorded as released)
+        for (int64_t k = 0; k < got; ++k) set_state(out[k], kFree);
+        return fail(SLORA_ENOMEM, "free pages could not be found");
+    }
+    return SLORA_OK;
+}
+
+// Record the adapter and put its page list into the arena (a freed range of the same length is
+// reused).  Changes no page state; on failure nothing is recorded.
+static int32_t place_list(slora_pool *pool, int32_t adapter_id, int32_t rank, const int32_t *page_idx, int64_t want)
+{
+    int64_t off;
+    auto fl = pool->free_lists.find(want);
+    try {
+        if (want > 0 && fl != pool->free_lists.end() && !fl->second.empty()) {
+            off = fl->second.back();
+            fl->second.pop_back();
+        } else {
+            off = (int64_t)pool->arena.size();
+            if (off + want >= (int64_t(1) << 31)) return fail(SLORA_ENOMEM, "page-list arena would exceed 2^31 entries");
+            pool->arena.resize((size_t)(off + want));
+        }
+        pool->adapters.emplace(adapter_id, Adapter{rank, off});
+    } catch (const std::bad_alloc &) {
+        return fail(SLORA_ENOMEM, "out of host memory");
+    }
+    if (want > 0) {
+        std::memcpy(pool->arena.data() + off, page_idx, (size_t)want * sizeof(int32_t));
+        if (pool->dirty_hi <= pool->dirty_lo) {
+            pool->dirty_lo = off;
+            pool->dirty_hi = off + want;
+        } else {
+            if (off < pool->dirty_lo) pool->dirty_lo = off;
+            if (off + want > pool->dirty_hi) pool->dirty_hi = off + want;
+        }
+    }
+    return SLORA_OK;
+}
+
 extern "C" {
 
 const char *slora_last_error(void) { return last_error_cstr(); }
@@ -108,6 +182,7 @@ int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32
     p->n_slots = n_slots;
     p->max_rank = max_rank;
     p->device = dev;
+    p->n_free = n_pages;
     *out = p;
     return SLORA_OK;
 }
@@ -156,7 +231,8 @@ int32_t slora_pool_mark_kv(slora_pool *pool, const int32_t *page_idx, int64_t n,
     const int64_t marked = i;
     for (int64_t k = 0; k < marked; ++k) {
         uint8_t &s = pool->state[page_idx[k]];
-        s = (rc == SLORA_OK) ? (owned ? (uint8_t)kKv : (uint8_t)kFree) : (uint8_t)(s & 0x7f);
+        s &= 0x7f;
+        if (rc == SLORA_OK) pool->set_state(page_idx[k], owned ? (uint8_t)kKv : (uint8_t)kFree);
     }
     return rc;
 }
@@ -237,33 +313,9 @@ int32_t slora_adapter_load(slora_pool *pool, int32_t adapter_id, int32_t rank, c
     for (int64_t k = 0; k < i; ++k) pool->state[page_idx[k]] &= 0x7f;
     if (rc != SLORA_OK) return rc;
 
-    // place the list in the arena (reuse a freed range of the same length if there is one)
-    int64_t off;
-    auto fl = pool->free_lists.find(want);
-    try {
-        if (want > 0 && fl != pool->free_lists.end() && !fl->second.empty()) {
-            off = fl->second.back();
-            fl->second.pop_back();
-        } else {
-            off = (int64_t)pool->arena.size();
-            if (off + want >= (int64_t(1) << 31)) return fail(SLORA_ENOMEM, "page-list arena would exceed 2^31 entries");
-            pool->arena.resize((size_t)(off + want));
-        }
-        pool->adapters.emplace(adapter_id, Adapter{rank, off});
-    } catch (const std::bad_alloc &) {
-        return fail(SLORA_ENOMEM, "out of host memory");
-    }
-    if (want > 0) {
-        std::memcpy(pool->arena.data() + off, page_idx, (size_t)want * sizeof(int32_t));
-        for (int64_t k = 0; k < want; ++k) pool->state[page_idx[k]] = kAdapter;
-        if (pool->dirty_hi <= pool->dirty_lo) {
-            pool->dirty_lo = off;
-            pool->dirty_hi = off + want;
-        } else {
-            if (off < pool->dirty_lo) pool->dirty_lo = off;
-            if (off + want > pool->dirty_hi) pool->dirty_hi = off + want;
-        }
-    }
+    rc = place_list(pool, adapter_id, rank, page_idx, want);
+    if (rc != SLORA_OK) return rc;
+    for (int64_t k = 0; k < want; ++k) pool->set_state(page_idx[k], kAdapter);
     return SLORA_OK;
 }
 
@@ -275,7 +327,7 @@ int32_t slora_adapter_unload(slora_pool *pool, int32_t adapter_id)
     if (it == pool->adapters.end()) return fail(SLORA_ENOENT, "adapter %d is not loaded", adapter_id);
     const int64_t len = (int64_t)pool->n_slots * 2 * it->second.rank;
     const int64_t off = it->second.arena_off;
-    for (int64_t k = 0; k < len; ++k) pool->state[pool->arena[(size_t)(off + k)]] = kFree;
+    for (int64_t k = 0; k < len; ++k) pool->set_state(pool->arena[(size_t)(off + k)], kFree);
     if (len > 0) {
         try {
             pool->free_lists[len].push_back(off);
@@ -304,6 +356,75 @@ int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot,
     if (r == 0) return SLORA_OK;
     const int64_t entry = it->second.arena_off + ((int64_t)slot * 2 + which) * r;
     return launch_gather(pool, entry, r, dev_out, stream);
+}
+
+int32_t slora_pool_free_pages(const slora_pool *pool, int64_t *out)
+{
+    clear_error();
+    if (!pool || !out) return fail(SLORA_EINVAL, "NULL argument");
+    *out = pool->n_free;
+    return SLORA_OK;
+}
+
+int32_t slora_pool_alloc_kv(slora_pool *pool, int64_t n, int32_t *out_idx)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    if (n < 0 || (n > 0 && !out_idx)) return fail(SLORA_EINVAL, "bad arguments");
+    return pool->take(n, kKv, out_idx);
+}
+
+int32_t slora_adapter_alloc(slora_pool *pool, int32_t adapter_id, int32_t rank, int32_t *out_idx)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    if (adapter_id < 0) return fail(SLORA_EINVAL, "adapter_id=%d must be >= 0", adapter_id);
+    if (rank < 0) return fail(SLORA_EINVAL, "rank=%d must be >= 0", rank);
+    if (rank > pool->max_rank) return fail(SLORA_ERANGE, "rank=%d exceeds max_rank=%d", rank, pool->max_rank);
+    if (pool->adapters.count(adapter_id)) return fail(SLORA_EBUSY, "adapter %d is already loaded", adapter_id);
+    const int64_t want = (int64_t)pool->n_slots * 2 * rank;
+    std::vector<int32_t> pages;
+    try {
+        pages.resize((size_t)want);
+    } catch (const std::bad_alloc &) {
+        return fail(SLORA_ENOMEM, "out of host memory");
+    }
+    int32_t rc = pool->take(want, kAdapter, pages.data());
+    if (rc != SLORA_OK) return rc;
+    rc = place_list(pool, adapter_id, rank, pages.data(), want);
+    if (rc != SLORA_OK) { // out of host memory for the list: the pages are free again
+        std::string keep = last_error_cstr();
+        for (int64_t k = 0; k < want; ++k) pool->set_state(pages[(size_t)k], kFree);
+        return fail(rc, "%s", keep.c_str());
+    }
+    if (out_idx && want > 0) std::memcpy(out_idx, pages.data(), (size_t)want * sizeof(int32_t));
+    return SLORA_OK;
+}
+
+int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *weights, void *stream)
+{
+    clear_error();
+    if (!pool) return fail(SLORA_EINVAL, "pool is NULL");
+    auto it = pool->adapters.find(adapter_id);
+    if (it == pool->adapters.end()) return fail(SLORA_ENOENT, "adapter %d is not loaded", adapter_id);
+    if (!pool->dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
+    const int64_t n = (int64_t)pool->n_slots * 2 * it->second.rank;
+    if (n == 0) return SLORA_OK;
+    if (!weights) return fail(SLORA_EINVAL, "weights is NULL");
+    HIP_TRY(hipSetDevice(pool->device));
+    // the copy kernel dereferences `weights` on the GPU: accept only memory the runtime knows
+    // (pinned host memory or device memory), never a pageable host pointer
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, weights);
+    if (e != hipSuccess || (attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeDevice &&
+                            attr.type != hipMemoryTypeManaged) || !attr.devicePointer) {
+        (void)hipGetLastError();
+        return fail(SLORA_EINVAL, "weights must be pinned host memory (hipHostMalloc) or device memory");
+    }
+    if (reinterpret_cast<uintptr_t>(attr.devicePointer) & 15) return fail(SLORA_EINVAL, "weights must be 16-byte aligned");
+    int32_t rc = pool->sync_device();
+    if (rc != SLORA_OK) return rc;
+    return launch_write_pages(pool, pool->d_arena + it->second.arena_off, n, attr.devicePointer, stream);
 }
 
 int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)

@@ -87,6 +87,11 @@ struct slora_pool {
     int32_t *d_arena = nullptr;                       // device image
     int64_t d_arena_cap = 0;                          // entries
     int64_t dirty_lo = 0, dirty_hi = 0;               // [lo, hi) not yet on the device
+    // allocator: pages are handed out from a stack of released pages first (entries are checked
+    // when popped: a page may have been taken by index meanwhile), then from the never-used tail
+    std::vector<int32_t> released;
+    int64_t fresh = 0;                                // pages >= fresh never entered `released`
+    int64_t n_free = 0;
     uint64_t unload_generation = 0;
     int64_t live_plans = 0;
     int64_t mfma_min_tokens = 16;
@@ -94,6 +99,8 @@ struct slora_pool {
     int64_t xcd_group = 0;
 
     int32_t sync_device();                            // push dirty arena range
+    void set_state(int64_t page, uint8_t to);         // ownership change with free-count / stack upkeep
+    int32_t take(int64_t n, uint8_t as, int32_t *out); // n free pages -> state `as`
 };
 
 struct slora_plan {

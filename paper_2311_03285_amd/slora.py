@@ -54,6 +54,10 @@ def lib() -> C.CDLL:
             "slora_adapter_load": (i32, [vp, i32, i32, vp, i64]),
             "slora_adapter_unload": (i32, [vp, i32]),
             "slora_adapter_gather": (i32, [vp, i32, i32, i32, vp, vp]),
+            "slora_pool_free_pages": (i32, [vp, vp]),
+            "slora_pool_alloc_kv": (i32, [vp, i64, vp]),
+            "slora_adapter_alloc": (i32, [vp, i32, i32, vp]),
+            "slora_adapter_upload": (i32, [vp, i32, vp, vp]),
             "slora_batch_plan": (i32, [vp, C.POINTER(vp), vp, i32, vp, i32]),
             "slora_plan_destroy": (i32, [vp]),
             "slora_plan_info": (i32, [vp, vp, i32]),
@@ -131,6 +135,32 @@ def pool_write_pages(pool, page_idx, src, src_on_device: bool, stream=None) -> N
 def adapter_load(pool, adapter_id: int, rank: int, page_idx) -> None:
     a = _i32(page_idx).reshape(-1)
     _check(lib().slora_adapter_load(pool, adapter_id, rank, _ptr(a) if a.size else None, a.size))
+
+
+def pool_free_pages(pool) -> int:
+    n = np.zeros(1, dtype=np.int64)
+    _check(lib().slora_pool_free_pages(pool, _ptr(n)))
+    return int(n[0])
+
+
+def pool_alloc_kv(pool, n: int) -> np.ndarray:
+    """n free pages become KV pages; returns their indices."""
+    out = np.zeros(max(int(n), 1), dtype=np.int32)
+    _check(lib().slora_pool_alloc_kv(pool, int(n), _ptr(out)))
+    return out[:int(n)]
+
+
+def adapter_alloc(pool, adapter_id: int, rank: int, n_slots: int) -> np.ndarray:
+    """Make the adapter resident on pages the library chooses; returns them as [n_slots, 2, rank]."""
+    out = np.zeros(max(n_slots * 2 * rank, 1), dtype=np.int32)
+    _check(lib().slora_adapter_alloc(pool, adapter_id, rank, _ptr(out)))
+    return out[:n_slots * 2 * rank].reshape(n_slots, 2, rank)
+
+
+def adapter_upload(pool, adapter_id: int, weights: int, stream=None) -> None:
+    """weights: address of pinned host or device memory laid out [slot][A columns][B rows][H]."""
+    _check(lib().slora_adapter_upload(pool, adapter_id, C.c_void_p(int(weights)) if weights else None,
+                                      _stream(stream)))
 
 
 def adapter_unload(pool, adapter_id: int) -> None:
