@@ -239,6 +239,57 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                          "passes per step",
                "gpu_vs_oracle_rel_l2": rel, "gpu_vs_oracle_max_abs": mx}
 
+    fetch = None
+    if args.fetch:
+        # adapters of waiting requests arriving from pinned host memory on a side stream while the
+        # steps run (Sec. 5.2): step time alone / under the fetch, fetch rate alone / under the steps
+        rank, n_new = 64, args.fetch
+        per_adapter = w0.n_slots * 2 * rank
+        free = np.ones(w0.n_pages, dtype=bool)
+        free[w0.owned_pages()] = False
+        give = np.nonzero(free)[0][:n_new * per_adapter].astype(np.int32)      # KV pages handed back
+        slora.pool_mark_kv(dw.pool, give, False)
+        host = (torch.randn((n_new, per_adapter, w0.H)) * 0.02).to(torch.float16).view(torch.int16).pin_memory()
+        new_ids = [w0.n_adapters + 1000 + i for i in range(n_new)]
+        for a in new_ids:
+            slora.adapter_alloc(dw.pool, a, rank, w0.n_slots)
+        side = torch.cuda.Stream(device=dev)
+        fetch_bytes = n_new * per_adapter * w0.H * 2
+
+        def fetch_all():
+            for i, a in enumerate(new_ids):
+                slora.adapter_upload(dw.pool, a, host[i].data_ptr(), side)
+
+        def timed(do_steps, do_fetch, reps=3):
+            best_s, best_f = None, None
+            for _ in range(reps):
+                s0, s1, f0, f1 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+                torch.cuda.synchronize()
+                n_steps = 8 * R
+                s0.record(stream)
+                if do_steps:            # enqueued first: the GPU is busy with them while the host
+                    for i in range(n_steps):        # issues the uploads
+                        step(i % R)
+                s1.record(stream)
+                f0.record(side)
+                if do_fetch:
+                    fetch_all()
+                f1.record(side)
+                torch.cuda.synchronize()
+                ts, tf = s0.elapsed_time(s1) / n_steps, f0.elapsed_time(f1)
+                best_s = ts if best_s is None else min(best_s, ts)
+                best_f = tf if best_f is None else min(best_f, tf)
+            return best_s, best_f
+
+        timed(True, True, 1)
+        s_alone, _ = timed(True, False)
+        _, f_alone = timed(False, True)
+        s_both, f_both = timed(True, True)
+        fetch = {"adapters": n_new, "rank": rank, "bytes": fetch_bytes,
+                 "fetch_ms_alone": round(f_alone, 4), "fetch_gbps_alone": round(fetch_bytes / f_alone / 1e6, 1),
+                 "fetch_ms_under_compute": round(f_both, 4),
+                 "step_ms_alone": round(s_alone, 5), "step_ms_under_fetch": round(s_both, 5)}
+
     out = {
         "metric": "lora_tokens_per_s", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -256,6 +307,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "event_ms_per_step": round(ev_ms / args.steps, 5),
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if fetch:
+        out["fetch"] = fetch
     dw.close()
     return out
 
@@ -269,6 +322,9 @@ def main() -> int:
     ap.add_argument("--law", default="power", choices=["power", "zipf"])
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--fetch", type=int, default=0,
+                    help="also time the upload of this many rank-64 adapters from pinned host memory on a side "
+                         "stream, alone and while the steps run")
     ap.add_argument("--y16", action="store_true",
                     help="y in the pool's 16-bit storage type (rounded once at the store) instead of fp32")
     ap.add_argument("--shared-x", action="store_true",

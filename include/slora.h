@@ -222,6 +222,9 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  *   "mfma_min_tiles"   the MFMA kernels are used only if such groups make up at least this many
  *                      32-token tiles in the batch (default 32: fewer tiles cannot fill the GPU
  *                      and run faster on the vector kernels)
+ *   "upload_groups"    workgroups of slora_adapter_upload when the source is host memory (default
+ *                      32: enough requests in flight to fill the host link; many more delay the
+ *                      HBM traffic of kernels running on other streams)
  *   "xcd_group"        0 (default): MFMA work items go to the 8 accelerator dies round-robin;
  *                      1: each die gets a contiguous, equally heavy run of the list, so all tiles
  *                      of an adapter share one L2 (fewer HBM reads, but measured slower here)

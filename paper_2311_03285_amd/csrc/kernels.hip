@@ -144,12 +144,15 @@ __device__ __forceinline__ float wave_sum(float v)
 // page scatter / gather (exact copies)
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void write_pages_kernel(uint16_t *__restrict__ pool, const int32_t *__restrict__ idx,
-                                                           const uint16_t *__restrict__ src, int H)
+                                                           const uint16_t *__restrict__ src, int H, int64_t n)
 {
-    const int64_t i = blockIdx.x;
-    const u32x4 *s = reinterpret_cast<const u32x4 *>(src + i * H);
-    u32x4 *d = reinterpret_cast<u32x4 *>(pool + (int64_t)idx[i] * H);
-    for (int c = threadIdx.x; c < H / 8; c += blockDim.x) d[c] = s[c];
+    // workgroups stride over the pages: a small grid bounds the requests in flight when the
+    // source is host memory behind the host link
+    for (int64_t i = blockIdx.x; i < n; i += gridDim.x) {
+        const u32x4 *s = reinterpret_cast<const u32x4 *>(src + i * H);
+        u32x4 *d = reinterpret_cast<u32x4 *>(pool + (int64_t)idx[i] * H);
+        for (int c = threadIdx.x; c < H / 8; c += blockDim.x) d[c] = s[c];
+    }
 }
 
 __global__ __launch_bounds__(256) void gather_pages_kernel(const uint16_t *__restrict__ pool,
@@ -882,13 +885,15 @@ int32_t check_launch(const char *what)
 // ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
-int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, const void *d_src, void *stream)
+int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, const void *d_src, void *stream,
+                           int32_t max_groups)
 {
     if (n <= 0) return SLORA_OK;
     if (n >= (int64_t(1) << 31)) return fail(SLORA_EINVAL, "too many pages in one call");
     if (reinterpret_cast<uintptr_t>(d_src) & 15) return fail(SLORA_EINVAL, "src must be 16-byte aligned");
-    hipLaunchKernelGGL(write_pages_kernel, dim3((unsigned)n), dim3(256), 0, (hipStream_t)stream,
-                       static_cast<uint16_t *>(pool->dev_base), d_idx, static_cast<const uint16_t *>(d_src), pool->H);
+    const int64_t groups = max_groups > 0 && n > max_groups ? max_groups : n;
+    hipLaunchKernelGGL(write_pages_kernel, dim3((unsigned)groups), dim3(256), 0, (hipStream_t)stream,
+                       static_cast<uint16_t *>(pool->dev_base), d_idx, static_cast<const uint16_t *>(d_src), pool->H, n);
     return check_launch("write_pages");
 }
 

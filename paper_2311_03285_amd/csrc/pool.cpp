@@ -424,7 +424,10 @@ int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *w
     if (reinterpret_cast<uintptr_t>(attr.devicePointer) & 15) return fail(SLORA_EINVAL, "weights must be 16-byte aligned");
     int32_t rc = pool->sync_device();
     if (rc != SLORA_OK) return rc;
-    return launch_write_pages(pool, pool->d_arena + it->second.arena_off, n, attr.devicePointer, stream);
+    // from host memory a few workgroups saturate the link; more only queue requests in front of
+    // the HBM traffic of kernels on other streams
+    const int32_t groups = attr.type == hipMemoryTypeDevice ? 0 : (int32_t)pool->upload_groups;
+    return launch_write_pages(pool, pool->d_arena + it->second.arena_off, n, attr.devicePointer, stream, groups);
 }
 
 int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
@@ -439,6 +442,11 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
     if (!std::strcmp(key, "mfma_min_tiles")) {
         if (value < 1) return fail(SLORA_EINVAL, "mfma_min_tiles must be >= 1");
         pool->mfma_min_tiles = value;
+        return SLORA_OK;
+    }
+    if (!std::strcmp(key, "upload_groups")) {
+        if (value < 1 || value > 65535) return fail(SLORA_EINVAL, "upload_groups must be in [1, 65535]");
+        pool->upload_groups = value;
         return SLORA_OK;
     }
     if (!std::strcmp(key, "xcd_group")) {

@@ -97,6 +97,7 @@ struct slora_pool {
     int64_t mfma_min_tokens = 16;
     int64_t mfma_min_tiles = 32;
     int64_t xcd_group = 0;
+    int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
 
     int32_t sync_device();                            // push dirty arena range
     void set_state(int64_t page, uint8_t to);         // ownership change with free-count / stack upkeep
@@ -146,7 +147,7 @@ int32_t build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids, int32
 
 // kernel launchers (kernels.hip); all return a SLORA_* code
 int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, const void *d_src,
-                           void *stream);
+                           void *stream, int32_t max_groups = 0); // max_groups > 0 caps the grid
 int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void *dev_out, void *stream);
 int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
 int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16);
