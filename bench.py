@@ -290,6 +290,80 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                  "fetch_ms_under_compute": round(f_both, 4),
                  "step_ms_alone": round(s_alone, 5), "step_ms_under_fetch": round(s_both, 5)}
 
+    ablation = None
+    if args.ablation:
+        # (1) the padded batched-matmul formulation the paper compares its kernels with
+        #     (Sec. 7.1, "bmm"): gather every token's adapter from the pool into contiguous
+        #     tensors padded to the largest rank, then two torch.bmm calls; (2) the base
+        #     projection x W on a second stream while the LoRA step runs (Fig. 1: the two are
+        #     independent until the add).  Library GEMMs only; slot 0 of batch 0.
+        tdt = torch.float16 if w0.dtype == 0 else torch.bfloat16
+        pool16 = dw.pool_t.view(tdt)
+        free = np.ones(w0.n_pages, dtype=bool)
+        free[w0.owned_pages()] = False
+        zero_page = int(np.nonzero(free)[0][0])                  # a KV page of this bench's pool
+        slora.pool_write_pages(dw.pool, [zero_page], np.zeros((1, w0.H), np.uint16), False)
+        act = np.nonzero(w0.ids >= 0)[0]
+        rmax = int(w0.ranks[w0.ids[act]].max())
+        ia = np.full((act.size, rmax), zero_page, dtype=np.int64)
+        ib = np.full((act.size, rmax), zero_page, dtype=np.int64)
+        for k, t in enumerate(act):
+            pg = w0.page_idx[int(w0.ids[t])][0]
+            ia[k, :pg.shape[1]] = pg[0]
+            ib[k, :pg.shape[1]] = pg[1]
+        ia_d, ib_d = torch.from_numpy(ia).to(dev), torch.from_numpy(ib).to(dev)
+        act_d = torch.from_numpy(act).to(dev)
+        x16 = xs[0][0].view(tdt)
+        y32 = ys[0][0].float() if args.y16 else ys[0][0].clone()
+
+        def bmm_step():
+            At = pool16[ia_d]                                       # [T, rmax, H]: rows = columns of A
+            Bm = pool16[ib_d]                                       # [T, rmax, H]
+            xv = x16[act_d].unsqueeze(1)                            # [T, 1, H]
+            v = torch.bmm(xv, At.transpose(1, 2))                   # [T, 1, rmax]
+            y32[act_d] += torch.bmm(v, Bm).squeeze(1).float()
+
+        def time_on(st, fn, reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(st):
+                fn()
+                torch.cuda.synchronize()
+                a.record(st)
+                for _ in range(reps):
+                    fn()
+                b.record(st)
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        t_bmm = time_on(stream, bmm_step, 5)
+        one_slot = lambda: apply_one(plans[0], 0, x_of(0, 0), ys[0][0].data_ptr(), stream)
+        t_ours = time_on(stream, one_slot, 20)
+        # base projection of the whole batch on a second stream
+        W = (torch.randn((w0.H, w0.H), device=dev) * 0.02).to(tdt)
+        xw = torch.empty((x16.shape[0], w0.H), dtype=tdt, device=dev)
+        side = torch.cuda.Stream(device=dev)
+        gemm = lambda: torch.matmul(x16, W, out=xw)
+        t_gemm = time_on(side, lambda: [gemm() for _ in range(n_slots)], 20)
+        t_step = time_on(stream, lambda: step(0), 20)
+        a0, a1, g1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        torch.cuda.synchronize()
+        a0.record(stream)
+        side.wait_event(a0)
+        for _ in range(20):
+            step(0)
+            with torch.cuda.stream(side):
+                for _ in range(n_slots):
+                    gemm()
+        a1.record(stream)
+        g1.record(side)
+        torch.cuda.synchronize()
+        t_both = max(a0.elapsed_time(a1), a0.elapsed_time(g1)) / 20
+        ablation = {"padded_bmm_ms_per_slot": round(t_bmm, 4), "lora_kernels_ms_per_slot": round(t_ours, 4),
+                    "padded_bmm_rank": rmax, "speedup_over_padded_bmm": round(t_bmm / t_ours, 2),
+                    "base_gemm_ms_per_step": round(t_gemm, 4), "lora_ms_per_step": round(t_step, 4),
+                    "both_streams_ms_per_step": round(t_both, 4),
+                    "serial_ms_per_step": round(t_gemm + t_step, 4)}
+
     out = {
         "metric": "lora_tokens_per_s", "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
@@ -309,6 +383,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     }
     if fetch:
         out["fetch"] = fetch
+    if ablation:
+        out["ablation"] = ablation
     dw.close()
     return out
 
@@ -322,6 +398,9 @@ def main() -> int:
     ap.add_argument("--law", default="power", choices=["power", "zipf"])
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the padded torch.bmm formulation of one slot and the base projection "
+                         "x W running on a second stream beside the LoRA step")
     ap.add_argument("--fetch", type=int, default=0,
                     help="also time the upload of this many rank-64 adapters from pinned host memory on a side "
                          "stream, alone and while the steps run")
