@@ -25,9 +25,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the counter reads for the library's plain page-copy kernel of known size
-# (profiles/cfg4_decode_hbm_traffic.md); only for the default command line.
+# (profiles/cfg4_decode_hbm_traffic.md); only for the default command lines of these workloads
+# with fp32 y.
 MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 321874 * 1024,
-                                                                        "shrink_vec": 301755 * 1024}}
+                                                                        "shrink_vec": 301755 * 1024},
+                    # profiles/cfg3_prefill_hbm_traffic.md
+                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 666887 * 1024,
+                                                            "shrink_mfma": 293524 * 1024}}
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
 
 
@@ -192,7 +196,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     roofline = {
         "bound": "hbm", "kernel": f"{dom}_{kinds}", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC.get((w0.name, args.law, args.mode, R), {}).get(f"{dom}_{kinds}"),
+        "traffic": (None if args.y16 or args.shared_x or args.opt else
+                    MEASURED_TRAFFIC.get((w0.name, args.law, args.mode, R), {}).get(f"{dom}_{kinds}")),
         "algorithmic_bytes_per_launch": int((ex_b if dom == "expand" else sh_b) * min(n_slots, slora.MAX_MULTI)),
         "avg_launch_us": round((ex_t if dom == "expand" else sh_t) * 1e6, 2),
         "other_kernel": {"kernel": f"{'shrink' if dom == 'expand' else 'expand'}_{kinds}",
