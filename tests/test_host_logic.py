@@ -96,6 +96,11 @@ def test_plan_validation():
     plan = slora.batch_plan(p, [0, 0, 1], [0, 2, 3])
     assert code(slora.lora_apply, plan, 0, 16, 16) == slora.EHIP                  # host-only pool
     assert code(slora.lora_apply, plan, 1, 16, 16) == slora.ERANGE                # slot
+    # the 16-bit-y entry points validate the same way
+    assert code(slora.lora_apply_multi_y16, plan, [0], [16], [16]) == slora.EHIP
+    assert code(slora.lora_apply_multi_y16, plan, [2], [16], [16]) == slora.ERANGE
+    assert code(slora.lora_apply_multi_y16, plan, [0] * 9, [16] * 9, [16] * 9) == slora.EINVAL   # more than 8 slots
+    assert code(slora.lora_expand_y16, plan, [0], [16]) == slora.EHIP
     slora.plan_destroy(plan)
     empty = slora.batch_plan(p, [])
     assert slora.plan_info(empty)["tokens"] == 0
