@@ -157,3 +157,14 @@ def test_config4_decode_full_size_y16():
         for k, slot in enumerate(slots):
             ref, exact = oracle_y16(w, slot)
             assert_y16_close(got[k], ref, exact, w.y16_bits(slot), w.dtype, f"cfg4 slot {slot}")
+
+
+def test_config5_mixed_full_size_y16():
+    """bfloat16, prefill requests and decode tokens in one batch: both kernel families in one call."""
+    w = synth.config(5)
+    slots = [0, 15]
+    with DeviceWorkload(w, real_adapters="used", slots=slots) as dw:
+        got = gpu_y16(dw, slots)
+        for k, slot in enumerate(slots):
+            ref, exact = oracle_y16(w, slot)
+            assert_y16_close(got[k], ref, exact, w.y16_bits(slot), w.dtype, f"cfg5 slot {slot}")
