@@ -67,8 +67,11 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         slora.set_option(dw.pool, k, int(v))
     stream = torch.cuda.Stream(device=dev)
     plans, xs, ys = [], [], []
+    plan_s = []
     for b, w in enumerate(wls):
-        plans.append(dw.plan(ids=w.ids, seg_offsets=w.seg_offsets))
+        tp = time.perf_counter()
+        plans.append(dw.plan(ids=w.ids, seg_offsets=w.seg_offsets))    # host scheduler + work-list upload
+        plan_s.append(time.perf_counter() - tp)
         # one activation buffer per projection (q, k, v would share theirs in a model; separate
         # buffers keep cache hits on x from flattering the byte rate) and one y per slot
         xs.append([bits_to_device(w.x_bits(s), dev) for s in range(min(n_slots, 4))])
@@ -141,6 +144,21 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     wall = time.perf_counter() - t0
     ev_ms = e0.elapsed_time(e1)
     ms_per_step = wall * 1e3 / args.steps
+
+    def per_step_ms(batches, n):
+        """Each step bracketed by its own pair of events: (median, min) in ms."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record(stream)
+        for i in range(n):
+            step(batches[i % len(batches)])
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+        return d[n // 2], d[0]
+
+    cold_med, cold_min = per_step_ms(list(range(R)), max(R, min(args.steps, 64)))
+    per_step_ms([0], 8)
+    warm_med, warm_min = per_step_ms([0], 32)       # the same batch again and again: caches help
     tok_per_step = float(np.mean([w.T for w in wls]))
     bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
     t_act_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H for w in wls]))
@@ -151,6 +169,9 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         x_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H * 2 for w in wls]))
         bytes_step -= x_b * sum(1 for s in range(n_slots) if s % 4 in (1, 2))
     flops_step = float(np.mean([w.flops() for w in wls])) * n_slots
+    # the same traffic if every token fetched its adapter's pages for itself (no sharing)
+    naive_step = float(np.mean([int(2 * w.ranks[w.ids[w.ids >= 0]].astype(np.int64).sum()) * w.H * 2 +
+                                np.count_nonzero(w.ids >= 0) * w.H * (2 + 8) for w in wls])) * n_slots
     value = tok_per_step * args.steps / wall
 
     # ---- per-kernel durations: HIP events on the launch stream around runs of one stage ----------
@@ -236,12 +257,20 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                 c_oracle.lora_apply(rows, w.dtype, lists, w.ids, xb, yb)
             t_cpu += time.perf_counter() - tc
             passes += 1
+        # one thread, a bounded sample: the first tokens of batch 0 on the first seeded slot
+        s1, (rows1, lists1), xb1, yb1 = packs[0]
+        k1 = int(min(w.T, 32))
+        tc = time.perf_counter()
+        c_oracle.lora_apply(rows1, w.dtype, lists1, w.ids[:k1], xb1[:k1], yb1[:k1], n_threads=1)
+        t_one = time.perf_counter() - tc
         pairs = passes * len(packs) * w.T                       # (token, slot) units done
         cpu = {"value": round(pairs / t_cpu / n_slots, 2), "unit": "tokens/s", "cores": int(cores),
                "kind": "oracle",
                "sample": f"{passes} pass(es) over the {w.T} tokens of batch 0 x {len(packs)} slot(s): "
                          f"{t_cpu:.2f}s wall on {cores} threads, scaled to the {n_slots} slots a token "
                          "passes per step",
+               "value_1_thread": round(k1 / t_one / n_slots, 2),
+               "sample_1_thread": f"{k1} tokens x 1 slot in {t_one:.2f}s on 1 thread, scaled the same way",
                "gpu_vs_oracle_rel_l2": rel, "gpu_vs_oracle_max_abs": mx}
 
     fetch = None
@@ -384,6 +413,11 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "mfma_util": round(flops_step / (wall / args.steps) / 1e12 / MFMA_PEAK_TFLOPS, 5),
         "algorithmic_bytes_per_step": int(bytes_step), "flops_per_step": int(flops_step),
         "event_ms_per_step": round(ev_ms / args.steps, 5),
+        "step_ms_median": round(cold_med, 5), "step_ms_min": round(cold_min, 5),
+        "warm_step_ms_median": round(warm_med, 5), "warm_step_ms_min": round(warm_min, 5),
+        "plan_ms": round(float(np.median(plan_s)) * 1e3, 4),
+        "ms_per_step_with_plan": round(ms_per_step + float(np.median(plan_s)) * 1e3, 5),
+        "naive_bytes_per_step": int(naive_step),
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if fetch:
@@ -428,7 +462,8 @@ def main() -> int:
     try:
         out = measure(args, args.workload, args.no_cpu)
         if args.workload == 4 and args.also != "none":
-            keep = ("value", "unit", "ms_per_step", "hbm_gbps", "hbm_frac", "mfma_util", "config", "roofline")
+            keep = ("value", "unit", "ms_per_step", "step_ms_median", "step_ms_min", "warm_step_ms_median",
+                    "plan_ms", "hbm_gbps", "hbm_frac", "mfma_util", "config", "roofline")
             out["also"] = []
             for n in (int(v) for v in args.also.split(",")):
                 o = measure(args, n, True)
