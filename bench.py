@@ -324,6 +324,23 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                  "fetch_ms_under_compute": round(f_both, 4),
                  "step_ms_alone": round(s_alone, 5), "step_ms_under_fetch": round(s_both, 5)}
 
+    # what a plain streaming copy reaches on this machine (torch's elementwise copy of 1 GiB: read +
+    # write), as a measured companion to the nominal 8 TB/s
+    a_ = torch.empty(1 << 30, dtype=torch.int8, device=dev)
+    b_ = torch.empty_like(a_)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        b_.copy_(a_)
+        c0.record(stream)
+        for _ in range(5):
+            b_.copy_(a_)
+        c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * a_.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del a_, b_
+    roofline["measured_copy_gbps"] = round(copy_gbs, 1)
+    roofline["frac_of_measured_copy"] = round(dom_gbs / copy_gbs, 4)
+
     ablation = None
     if args.ablation:
         # (1) the padded batched-matmul formulation the paper compares its kernels with
