@@ -168,3 +168,45 @@ def test_config5_mixed_full_size_y16():
         for k, slot in enumerate(slots):
             ref, exact = oracle_y16(w, slot)
             assert_y16_close(got[k], ref, exact, w.y16_bits(slot), w.dtype, f"cfg5 slot {slot}")
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_ties_round_to_even_on_the_device(dtype):
+    """x = e_0 and A's only column = e_0 give v = 1 exactly, so the delta is B's row: with y_in on a
+    16-bit grid point and B at half a spacing (and just beside it) the fp32 sum is exact and the
+    store must round it as IEEE 754 roundTiesToEven does - even neighbour on ties."""
+    H, dev = 64, torch.device("cuda:0")
+    p = 11 if dtype == synth.F16 else 8
+    half = 2.0 ** -p                                   # half the spacing of the format in [1, 2)
+    enc = (lambda a: np.asarray(a, np.float16).view(np.uint16)) if dtype == synth.F16 else \
+          (lambda a: (np.asarray(a, np.float32).view(np.uint32) >> 16).astype(np.uint16))
+    even, odd = 1.0, 1.0 + 2 * half                    # last significand bit 0 / 1
+    y_vals = np.tile([even, odd, -even, -odd, even, odd, even, odd], H // 8)
+    b_vals = np.tile([half, half, -half, -half, 1.5 * half, 1.5 * half, 0.5 * half, 0.5 * half], H // 8)
+    for v in (y_vals, b_vals):                         # all exactly representable in the 16-bit type
+        assert np.array_equal(c_oracle.widen(enc(v), dtype), v)
+    pool_bits = np.zeros((4, H), np.uint16)
+    e0 = np.zeros(H)
+    e0[0] = 1.0
+    pool_bits[2] = enc(e0)                             # A: its one column
+    pool_bits[1] = enc(b_vals)                         # B: its one row
+    pool_t = torch.from_numpy(pool_bits.view(np.int16)).to(dev)
+    pool = slora.pool_init(H, 4, dtype, pool_t.data_ptr(), 1, 1)
+    slora.adapter_load(pool, 0, 1, [2, 1])
+    ids = np.zeros(3, np.int32)
+    x = bits_to_device(np.tile(enc(e0), (3, 1)), dev)
+    yb = np.tile(enc(y_vals), (3, 1))
+    y = bits_to_device(yb, dev)
+    plan = slora.batch_plan(pool, ids, None)
+    slora.lora_apply_multi_y16(plan, [0], [x.data_ptr()], [y.data_ptr()])
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().view(np.uint16)
+    ref, exact = c_oracle.lora_apply_y16(pool_bits, dtype, {0: np.array([[2], [1]], np.int32)}, ids,
+                                         np.tile(enc(e0), (3, 1)), yb)
+    assert np.array_equal(exact[0], y_vals + b_vals)
+    # ties go to the even neighbour: 1 + h -> 1, (1 + 2h) + h -> 1 + 4h; 1.5 h rounds up, 0.5 h down
+    want = np.tile([even, odd + 2 * half, -even, -(odd + 2 * half), even + 2 * half, odd + 2 * half, even, odd], H // 8)
+    assert np.array_equal(ref[0], enc(want))
+    assert np.array_equal(got, ref)
+    slora.plan_destroy(plan)
+    slora.pool_destroy(pool)
