@@ -171,7 +171,8 @@ def test_config5_mixed_full_size_y16():
 
 
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
-def test_ties_round_to_even_on_the_device(dtype):
+@pytest.mark.parametrize("T", [3, 40])                 # vector kernels / MFMA kernels
+def test_ties_round_to_even_on_the_device(dtype, T):
     """x = e_0 and A's only column = e_0 give v = 1 exactly, so the delta is B's row: with y_in on a
     16-bit grid point and B at half a spacing (and just beside it) the fp32 sum is exact and the
     store must round it as IEEE 754 roundTiesToEven does - even neighbour on ties."""
@@ -193,20 +194,22 @@ def test_ties_round_to_even_on_the_device(dtype):
     pool_t = torch.from_numpy(pool_bits.view(np.int16)).to(dev)
     pool = slora.pool_init(H, 4, dtype, pool_t.data_ptr(), 1, 1)
     slora.adapter_load(pool, 0, 1, [2, 1])
-    ids = np.zeros(3, np.int32)
-    x = bits_to_device(np.tile(enc(e0), (3, 1)), dev)
-    yb = np.tile(enc(y_vals), (3, 1))
+    slora.set_option(pool, "mfma_min_tiles", 1)
+    ids = np.zeros(T, np.int32)
+    x = bits_to_device(np.tile(enc(e0), (T, 1)), dev)
+    yb = np.tile(enc(y_vals), (T, 1))
     y = bits_to_device(yb, dev)
     plan = slora.batch_plan(pool, ids, None)
+    assert (slora.plan_info(plan)["groups_mfma"] == 1) == (T >= 16)
     slora.lora_apply_multi_y16(plan, [0], [x.data_ptr()], [y.data_ptr()])
     torch.cuda.synchronize()
     got = y.cpu().numpy().view(np.uint16)
     ref, exact = c_oracle.lora_apply_y16(pool_bits, dtype, {0: np.array([[2], [1]], np.int32)}, ids,
-                                         np.tile(enc(e0), (3, 1)), yb)
-    assert np.array_equal(exact[0], y_vals + b_vals)
+                                         np.tile(enc(e0), (T, 1)), yb)
+    assert np.array_equal(exact[T - 1], y_vals + b_vals)
     # ties go to the even neighbour: 1 + h -> 1, (1 + 2h) + h -> 1 + 4h; 1.5 h rounds up, 0.5 h down
     want = np.tile([even, odd + 2 * half, -even, -(odd + 2 * half), even + 2 * half, odd + 2 * half, even, odd], H // 8)
-    assert np.array_equal(ref[0], enc(want))
+    assert np.array_equal(ref[T - 1], enc(want))
     assert np.array_equal(got, ref)
     slora.plan_destroy(plan)
     slora.pool_destroy(pool)
