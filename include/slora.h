@@ -173,6 +173,9 @@ int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n);
  * row-major, updated in place.  Asynchronous on `stream`; x and y must stay valid until the
  * stream has run the work.  Rows of tokens with id -1 or a rank-0 adapter are not accessed.
  * Results are deterministic: no floating-point atomics, fixed reduction order per plan.
+ * Once a plan has been applied with n slots, further applies with at most n slots allocate
+ * nothing and may be captured in a HIP graph; a replay stays valid until an adapter the plan
+ * uses is unloaded (the host-side checks of this call are not part of the graph).
  */
 int32_t slora_lora_apply(slora_plan *plan, int32_t slot, const void *x, float *y, void *stream);
 

@@ -251,16 +251,22 @@ int32_t slora_plan::ensure_v(int32_t n)
 {
     const int64_t need = (int64_t)n * v_slot_floats(pool->dtype);
     if (need <= d_v_cap) return SLORA_OK;
-    hipError_t e = hipSuccess;
-    if (d_v) {
-        e = hipDeviceSynchronize(); // earlier launches may still use the old scratch
-        if (e == hipSuccess) e = hipFree(d_v);
-        d_v = nullptr;
-        d_v_cap = 0;
-    }
-    if (e == hipSuccess) e = hipMalloc((void **)&d_v, (size_t)need * sizeof(float));
+    // Launches in flight and applies captured in a HIP graph hold the old scratch's address: it
+    // stays allocated until the plan is destroyed (a call with more slots than any before is rare).
+    float *fresh = nullptr;
+    hipError_t e = hipMalloc((void **)&fresh, (size_t)need * sizeof(float));
     if (e != hipSuccess) return hip_fail(e, "hipMalloc(v scratch)");
+    if (d_v) {
+        try {
+            retired_v.push_back(d_v);
+        } catch (const std::bad_alloc &) {
+            (void)hipFree(fresh);
+            return fail(SLORA_ENOMEM, "out of host memory");
+        }
+    }
+    d_v = fresh;
     d_v_cap = need;
+    v_slots = 0; // the new scratch holds no shrink result yet
     return SLORA_OK;
 }
 
@@ -372,6 +378,7 @@ int32_t slora_plan_destroy(slora_plan *plan)
         (void)hipDeviceSynchronize();
         if (plan->d_blob) (void)hipFree(plan->d_blob);
         if (plan->d_v) (void)hipFree(plan->d_v);
+        for (float *old_v : plan->retired_v) (void)hipFree(old_v);
     }
     plan->pool->live_plans--;
     delete plan;

@@ -53,12 +53,15 @@ int32_t slora_pool::sync_device()
         int32_t *fresh = nullptr;
         HIP_TRY(hipMalloc((void **)&fresh, (size_t)cap * sizeof(int32_t)));
         if (d_arena) {
-            // kernels that are still running may read the old image
-            hipError_t e = hipDeviceSynchronize();
-            if (e == hipSuccess) e = hipFree(d_arena);
-            if (e != hipSuccess) {
+            // Kernels in flight, and applies captured in a HIP graph, hold the old image's address:
+            // it stays allocated (and valid for every adapter loaded before this point) until
+            // the pool is destroyed.  Capacities double, so the retired images add up to less
+            // than the live one.
+            try {
+                retired_arenas.push_back(d_arena);
+            } catch (const std::bad_alloc &) {
                 (void)hipFree(fresh);
-                return hip_fail(e, "replacing the device page-list arena");
+                return fail(SLORA_ENOMEM, "out of host memory");
             }
         }
         d_arena = fresh;
@@ -196,6 +199,7 @@ int32_t slora_pool_destroy(slora_pool *pool)
         (void)hipSetDevice(pool->device);
         (void)hipDeviceSynchronize();
         (void)hipFree(pool->d_arena);
+        for (int32_t *old_image : pool->retired_arenas) (void)hipFree(old_image);
     }
     delete pool;
     return SLORA_OK;

@@ -86,6 +86,7 @@ struct slora_pool {
     std::unordered_map<int64_t, std::vector<int64_t>> free_lists; // length -> offsets
     int32_t *d_arena = nullptr;                       // device image
     int64_t d_arena_cap = 0;                          // entries
+    std::vector<int32_t *> retired_arenas;            // outgrown device images, freed with the pool
     int64_t dirty_lo = 0, dirty_hi = 0;               // [lo, hi) not yet on the device
     // allocator: pages are handed out from a stack of released pages first (entries are checked
     // when popped: a page may have been taken by index meanwhile), then from the never-used tail
@@ -133,6 +134,7 @@ struct slora_plan {
         return (int64_t)T_act * v_stride + (int64_t)n_mfma_tiles * (v_stride / 16) * (dtype == SLORA_F16 ? 2 : 3) * 256;
     }
     int64_t d_v_cap = 0;
+    std::vector<float *> retired_v; // outgrown scratch buffers, freed with the plan
     int32_t v_slots = 0;  // n of the latest shrink
 
     int32_t upload();
