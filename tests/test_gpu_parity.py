@@ -274,6 +274,40 @@ def test_apply_can_be_captured_in_a_hip_graph():
         assert_close(eager[0], oracle_slot(w, 0), "graph slot 0")
 
 
+def test_graph_replay_survives_table_growth():
+    """After the capture, more adapters are loaded (the device page-list table outgrows its
+    allocation) and the plan is applied with more slots than before (so does the v scratch): the
+    tables the captured launches point at must still be there, and still right, on replay."""
+    w = ragged_workload(309, synth.BF16, H=512, T=40, n_pages=8000)
+    with DeviceWorkload(w, real_adapters="all", mark_kv=False, max_rank=64) as dw:
+        plan = dw.plan()
+        x, y0 = dw.x_dev(0), dw.y_dev(0)
+        y = y0.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            slora.lora_apply(plan, 0, x.data_ptr(), y.data_ptr(), torch.cuda.current_stream())
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        eager = y.cpu().numpy()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            slora.lora_apply(plan, 0, x.data_ptr(), y.data_ptr(), torch.cuda.current_stream())
+        for a in range(100, 124):                       # 24 x 256 list entries: past the first 4096
+            slora.adapter_alloc(dw.pool, a, 64, w.n_slots)
+        xs, ys = [dw.x_dev(0), dw.x_dev(1)], [dw.y_dev(0), dw.y_dev(1)]
+        slora.lora_apply_multi(plan, [0, 1], [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+        torch.cuda.synchronize()
+        assert np.array_equal(ys[0].cpu().numpy(), eager)      # the regrown tables give the same bits
+        for rep in range(3):
+            y.copy_(y0)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy(), eager), rep
+        assert_close(eager, oracle_slot(w, 0), "graph after growth")
+
+
 def test_projections_sharing_one_x_buffer():
     """q, k, v of a layer read the same activations: one call over three slots with the same x
     pointer gives, per slot, the bits of that slot applied on its own (vector and MFMA paths)."""
