@@ -330,3 +330,51 @@ def test_projections_sharing_one_x_buffer():
                 assert np.array_equal(ys[s].cpu().numpy(), single[s].cpu().numpy())
                 # and against the oracle: slot s's weights, slot 0's activations
                 assert_close(ys[s].cpu().numpy(), oracle_slot(w, s, x_bits=w.x_bits(0)), f"shared x, slot {s}")
+
+
+# ------------------------------------------------------------------ seeded random shapes
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_against_the_oracle(seed):
+    """Seeded random batches inside the documented limits: H any multiple of 8 from 64 up, ranks
+    from 0 to 96 (two rank windows of the vector expand, two rank chunks of the MFMA shrink),
+    segments of 1 to 150 tokens, tokens without adapter, either storage type, the scheduler left
+    to route by itself or forced to one kernel family; fp32 and 16-bit y."""
+    g = np.random.default_rng(9000 + seed)
+    H = int(g.choice([64, 72, 200, 512, 1000, 1536, 2048, 4104]))
+    dtype = int(g.integers(0, 2))
+    n_ad = int(g.integers(1, 9))
+    ranks = tuple(int(r) for r in g.choice([0, 1, 2, 7, 8, 16, 31, 33, 64, 65, 96], size=n_ad))
+    n_seg = int(g.integers(1, 12))
+    lens = [int(v) for v in g.choice([1, 1, 1, 2, 3, 5, 17, 32, 33, 64, 70, 150], size=n_seg)]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_ad = g.integers(-1, n_ad, size=n_seg)
+    ids = np.repeat(seg_ad, lens).astype(np.int32)
+    n_slots = 2
+    n_pages = int(2 * n_slots * 2 * sum(ranks) + 16)
+    w = synth.make_workload("random", 9000 + seed, H, dtype, n_pages, n_slots, ranks, ids, seg)
+    route_kind = ["auto", "vec", "mfma"][seed % 3]
+    with DeviceWorkload(w, real_adapters="all", max_rank=96) as dw:
+        if route_kind == "vec":
+            slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY)
+        elif route_kind == "mfma":
+            slora.set_option(dw.pool, "mfma_min_tokens", 1)
+            slora.set_option(dw.pool, "mfma_min_tiles", 1)
+        plan = dw.plan()
+        untouched = (w.ids < 0) | (w.ranks[np.maximum(w.ids, 0)] == 0)
+        for slot in range(n_slots):
+            got = gpu_slot(dw, slot, plan)
+            assert np.array_equal(got[untouched], w.y_in(slot)[untouched])
+            if (~untouched).any():
+                assert_close(got, oracle_slot(w, slot), f"seed {seed} H={H} ranks={ranks} lens={lens} {route_kind}")
+        # the same batch with 16-bit y: within one 16-bit step of the fp32-y result, rounded
+        yb = bits_to_device(w.y16_bits(0), dw.device)
+        x = dw.x_dev(0)
+        slora.lora_apply_multi_y16(plan, [0], [x.data_ptr()], [yb.data_ptr()])
+        torch.cuda.synchronize()
+        got16 = yb.cpu().numpy().view(np.uint16).reshape(w.T, H)
+        assert np.array_equal(got16[untouched], w.y16_bits(0)[untouched])
+        dec = (lambda b: b.view(np.float16).astype(np.float64)) if dtype == synth.F16 else \
+              (lambda b: (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64))
+        ref = oracle_slot(w, 0, y_in=dec(w.y16_bits(0)).astype(np.float32))
+        tol = (2.0 ** -10 if dtype == synth.F16 else 2.0 ** -7) * np.maximum(np.abs(ref), 2.0 ** -14) + 1e-5
+        assert np.all(np.abs(dec(got16) - ref) <= tol)
