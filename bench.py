@@ -338,6 +338,22 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     torch.cuda.synchronize()
     copy_gbs = 5 * 2 * a_.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del a_, b_
+    # and what the library GEMM (hipBLASLt through torch) reaches on an 8192^3 product in the
+    # storage type, as a measured companion to the nominal dense MFMA peak
+    tdt_ = torch.float16 if w0.dtype == 0 else torch.bfloat16
+    ga = (torch.randn((8192, 8192), device=dev) * 0.01).to(tdt_)
+    gb = (torch.randn((8192, 8192), device=dev) * 0.01).to(tdt_)
+    gc = torch.empty((8192, 8192), dtype=tdt_, device=dev)
+    with torch.cuda.stream(stream):
+        torch.matmul(ga, gb, out=gc)
+        c0.record(stream)
+        for _ in range(5):
+            torch.matmul(ga, gb, out=gc)
+        c1.record(stream)
+    torch.cuda.synchronize()
+    gemm_tflops = 5 * 2 * 8192 ** 3 / (c0.elapsed_time(c1) * 1e-3) / 1e12
+    del ga, gb, gc
+    roofline["measured_gemm_tflops"] = round(gemm_tflops, 1)
     roofline["measured_copy_gbps"] = round(copy_gbs, 1)
     roofline["frac_of_measured_copy"] = round(dom_gbs / copy_gbs, 4)
 
