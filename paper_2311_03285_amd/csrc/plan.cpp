@@ -196,8 +196,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
             }
         }
-        xcd_layout(plan->ms_items, [H](const Item &i) { return (int64_t)(i.ntok + i.b) * H * 2; }, pool->xcd_group != 0);
-        xcd_layout(plan->me_items, [](const Item &i) { return (int64_t)i.b * (i.ntok * 8 + i.rank * 2); }, pool->xcd_group != 0);
+        xcd_layout(plan->ms_items, [H](const Item &i) { return (int64_t)(i.ntok + i.b) * H * 2; }, (pool->xcd_group & 1) != 0);
+        xcd_layout(plan->me_items, [](const Item &i) { return (int64_t)i.b * (i.ntok * 8 + i.rank * 2); }, (pool->xcd_group & 2) != 0);
         plan->T_act = (int32_t)plan->tok_idx.size();
         plan->v_stride = std::max(kRankPad, (max_rank + kRankPad - 1) / kRankPad * kRankPad);
     } catch (const std::bad_alloc &) {

@@ -454,7 +454,8 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
         return SLORA_OK;
     }
     if (!std::strcmp(key, "xcd_group")) {
-        pool->xcd_group = value != 0;
+        if (value < 0 || value > 3) return fail(SLORA_EINVAL, "xcd_group must be 0..3");
+        pool->xcd_group = value;
         return SLORA_OK;
     }
     return fail(SLORA_EINVAL, "unknown option '%s'", key);

@@ -97,7 +97,7 @@ struct slora_pool {
     int64_t live_plans = 0;
     int64_t mfma_min_tokens = 16;
     int64_t mfma_min_tiles = 32;
-    int64_t xcd_group = 0;
+    int64_t xcd_group = 0;                            // bit 0: MFMA shrink list grouped per XCD, bit 1: expand list
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
 
     int32_t sync_device();                            // push dirty arena range

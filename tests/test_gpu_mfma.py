@@ -158,9 +158,10 @@ def test_xcd_grouping_changes_the_schedule_not_the_result():
     w = prefill_workload(490, synth.F16, H=1000)
     with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
         route(dw.pool, MFMA_ALL)
+        slora.set_option(dw.pool, "xcd_group", 0)       # both lists round-robin over the dies
         a = gpu_slot(dw, 0, dw.plan())
-        slora.set_option(dw.pool, "xcd_group", 1)
-        p = dw.plan()
-        assert slora.plan_info(p)["mfma_shrink_items"] == slora.plan_info(dw.plans[0])["mfma_shrink_items"]
-        b = gpu_slot(dw, 0, p)
-        assert np.array_equal(a, b)
+        for mode in (1, 2, 3):                          # shrink list grouped, expand list, both
+            slora.set_option(dw.pool, "xcd_group", mode)
+            p = dw.plan()
+            assert slora.plan_info(p)["mfma_shrink_items"] == slora.plan_info(dw.plans[0])["mfma_shrink_items"]
+            assert np.array_equal(a, gpu_slot(dw, 0, p)), mode

@@ -137,7 +137,8 @@ def test_scheduler_groups_buckets_and_routes():
     assert slora.plan_info(plan)["groups_mfma"] == 0
     slora.plan_destroy(plan)
     slora.set_option(p, "mfma_min_tokens", 16)
-    slora.set_option(p, "xcd_group", 1)
+    slora.set_option(p, "xcd_group", 3)
+    assert code(slora.set_option, p, "xcd_group", 4) == slora.EINVAL
     plan = slora.batch_plan(p, ids, seg)
     grouped = slora.plan_info(plan)
     assert grouped["mfma_shrink_items"] == 1 and grouped["mfma_expand_items"] == 2 * (1024 // 256)
