@@ -78,8 +78,8 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         if (seg_offsets[n_seg] != T)
             return fail(SLORA_ESEG, "seg_offsets[n_seg]=%d must equal T=%d", seg_offsets[n_seg], T);
         for (int32_t s = 0; s < n_seg; ++s) {
-            if (seg_offsets[s + 1] <= seg_offsets[s])
-                return fail(SLORA_ESEG, "seg_offsets must be strictly increasing (segment %d)", s);
+            if (seg_offsets[s + 1] <= seg_offsets[s] || seg_offsets[s + 1] > T)
+                return fail(SLORA_ESEG, "seg_offsets must be strictly increasing and end at T (segment %d)", s);
             const int32_t id0 = ids[seg_offsets[s]];
             for (int32_t t = seg_offsets[s] + 1; t < seg_offsets[s + 1]; ++t)
                 if (ids[t] != id0)

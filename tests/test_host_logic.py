@@ -92,6 +92,7 @@ def test_plan_validation():
     assert code(slora.batch_plan, p, [0, 0, 1], [1, 2, 3]) == slora.ESEG          # does not start at 0
     assert code(slora.batch_plan, p, [0, 0, 1], [0, 2, 2, 3]) == slora.ESEG       # empty segment
     assert code(slora.batch_plan, p, [0, 0, 1], [0, 2]) == slora.ESEG             # does not end at T
+    assert code(slora.batch_plan, p, [0, 0, 1], [0, 1000000, 3]) == slora.ESEG    # an offset far past T
     assert code(slora.batch_plan, p, [0, 1, 1], [0, 2, 3]) == slora.ESEG          # mixed ids in a segment
     plan = slora.batch_plan(p, [0, 0, 1], [0, 2, 3])
     assert code(slora.lora_apply, plan, 0, 16, 16) == slora.EHIP                  # host-only pool
