@@ -165,3 +165,35 @@ def test_xcd_grouping_changes_the_schedule_not_the_result():
             p = dw.plan()
             assert slora.plan_info(p)["mfma_shrink_items"] == slora.plan_info(dw.plans[0])["mfma_shrink_items"]
             assert np.array_equal(a, gpu_slot(dw, 0, p)), mode
+
+
+def test_eight_slots_in_one_launch_pair():
+    """The largest launch shape (8 slots per call, as the mixed configuration is timed): every
+    slot gives the bits of that slot applied on its own, on a batch that uses both kernel
+    families; with 16-bit y as well."""
+    w = prefill_workload(495, synth.BF16, H=512, n_slots=8, n_pages=9000)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, 16)                     # groups of >= 16 tokens on MFMA, the rest on the vector kernels
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        assert info["groups_mfma"] > 0 and info["groups_vec"] > 0
+        slots = list(range(8))
+        single = [gpu_slot(dw, s, plan) for s in slots]
+        xs = [dw.x_dev(s) for s in slots]
+        ys = [dw.y_dev(s) for s in slots]
+        slora.lora_apply_multi(plan, slots, [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+        torch.cuda.synchronize()
+        for s in slots:
+            assert np.array_equal(ys[s].cpu().numpy(), single[s]), s
+        assert_close(single[7], oracle_slot(w, 7), "slot 7 of 8")
+        # 16-bit y: eight slots at once against one at a time
+        from paper_2311_03285_amd.harness import bits_to_device
+        y16 = [bits_to_device(w.y16_bits(s), dw.device) for s in slots]
+        slora.lora_apply_multi_y16(plan, slots, [t.data_ptr() for t in xs], [t.data_ptr() for t in y16])
+        one = bits_to_device(w.y16_bits(5), dw.device)
+        slora.lora_apply_multi_y16(plan, [5], [xs[5].data_ptr()], [one.data_ptr()])
+        torch.cuda.synchronize()
+        assert torch.equal(y16[5], one)
+        with pytest.raises(slora.SloraError):  # nine slots are refused before anything is launched
+            slora.lora_apply_multi(plan, slots + [0], [t.data_ptr() for t in xs + xs[:1]],
+                                   [t.data_ptr() for t in ys + ys[:1]])
