@@ -213,3 +213,21 @@ def test_ties_round_to_even_on_the_device(dtype, T):
     assert np.array_equal(got, ref)
     slora.plan_destroy(plan)
     slora.pool_destroy(pool)
+
+
+@pytest.mark.parametrize("path", ["vec", "mfma"])
+def test_extreme_shapes_y16(path):
+    """The largest page (H = 32768) and the largest rank (1024) with 16-bit y."""
+    cases = [
+        synth.make_workload("max-H", 905, 32768, synth.BF16, 128, 1, (8, 40),
+                            np.array([0, 1, 1, 0, 1, -1, 1, 1], dtype=np.int32)),
+        synth.make_workload("max-rank", 906, 256, synth.F16, 4200, 1, (1024, 1000),
+                            np.repeat([0, 1], [3, 40]).astype(np.int32), np.array([0, 3, 43], dtype=np.int32)),
+    ]
+    for w in cases:
+        with DeviceWorkload(w, real_adapters="all", max_rank=1024) as dw:
+            slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY if path == "vec" else 1)
+            slora.set_option(dw.pool, "mfma_min_tiles", 1)
+            got = gpu_y16(dw, [0])[0]
+            ref, exact = oracle_y16(w, 0)
+            assert_y16_close(got, ref, exact, w.y16_bits(0), w.dtype, f"{w.name} {path}")
