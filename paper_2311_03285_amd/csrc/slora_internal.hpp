@@ -51,7 +51,7 @@ struct MultiArgs {
 constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows staged in LDS)
 constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
-constexpr int kExpandColsMax = 3072; // most columns per vector-expand item (a multiple of 512, <= 4096)
+constexpr int kExpandColsMax = 1024; // most columns per vector-expand item (a multiple of 512, <= 4096; measured best on cfg4: 1024)
 constexpr int kMfmaTok = 32;      // tokens per v tile = per MFMA-expand item (one 32-row MFMA block)
 constexpr int kMfmaShrinkTiles = 2; // v tiles (32 tokens each) per MFMA-shrink item
 constexpr int kMfmaRanks = 64;    // ranks per MFMA-shrink item (two 32-column MFMA blocks)
