@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # scaled by what the counter reads for the library's plain page-copy kernel of known size
 # (profiles/cfg4_decode_hbm_traffic.md); only for the default command lines of these workloads
 # with fp32 y.
-MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 321874 * 1024,
-                                                                        "shrink_vec": 301755 * 1024},
+MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 324734 * 1024,
+                                                                        "shrink_vec": 304298 * 1024},
                     # profiles/cfg3_prefill_hbm_traffic.md
                     ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 666887 * 1024,
                                                             "shrink_mfma": 293524 * 1024}}
