@@ -402,9 +402,9 @@ __global__ __launch_bounds__(512) void expand_vec_kernel(const Item *__restrict_
     const bool live = col < col_end;
     const int32_t *pb = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.rank;
     if (it.ntok == 1)
-        expand_vec_body<DT, Y16, 1, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+        expand_vec_body<DT, Y16, 1, 8, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else if (it.ntok == 2)
-        expand_vec_body<DT, Y16, 2, 16, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
+        expand_vec_body<DT, Y16, 2, 8, true, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
     else
         expand_vec_body<DT, Y16, kExpandTok, 8, false, false>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, nullptr);
 }
