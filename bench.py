@@ -28,10 +28,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # (profiles/cfg4_decode_hbm_traffic.md); only for the default command lines of these workloads
 # with fp32 y.
 MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 324734 * 1024,
-                                                                        "shrink_vec": 304298 * 1024},
-                    # profiles/cfg3_prefill_hbm_traffic.md
+                                                                        "shrink_vec": 304298 * 1024,
+                                                                        "source": "profiles/cfg4_decode_hbm_traffic.md"},
                     ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 666887 * 1024,
-                                                            "shrink_mfma": 293524 * 1024}}
+                                                            "shrink_mfma": 293524 * 1024,
+                                                            "source": "profiles/cfg3_prefill_hbm_traffic.md"}}
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
 
 
@@ -58,7 +59,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     n_slots = w0.n_slots
     # the pool: every adapter loaded at its scattered pages; seeded weights for the adapters of
     # batch 0 (the oracle's sample uses them), finite filler for the rest, NaN on KV pages
-    dw = DeviceWorkload(w0, device=dev, real_adapters="used", slots=list(range(min(n_slots, 4))))
+    dw = DeviceWorkload(w0, device=dev, real_adapters="used", slots=list(range(n_slots)), threads=16)
     log(f"[bench] pool ready: {w0.name}, {w0.n_pages} pages x {w0.H} ({w0.n_pages * w0.H * 2 / 1e9:.1f} GB), "
         f"{w0.n_adapters} adapters, {n_slots} slots, setup {time.time() - t_setup:.1f}s")
 
@@ -160,9 +161,59 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         d = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
         return d[n // 2], d[0]
 
+    # ---- the per-batch life-cycle (Sec. 4.1: a new batch every iteration) ---------------------
+    # (a) plan + apply of every slot + plan_destroy per step, nothing waited for in between;
+    # (b) the one-shot call (plan + apply of ONE slot + destroy) back to back.  Wall clock per
+    # cycle including the final synchronisation, and the host's share of it (time until the
+    # calls of a cycle have returned).
+    def cycle(b):
+        p = slora.batch_plan(dw.pool, wls[b].ids, wls[b].seg_offsets)
+        for g0 in range(0, n_slots, slora.MAX_MULTI):
+            g = slots[g0:g0 + slora.MAX_MULTI]
+            apply_multi(p, g, [x_of(b, s) for s in g], [ys[b][s].data_ptr() for s in g], stream)
+        slora.plan_destroy(p)
+
+    def one_shot(b):
+        if args.y16:
+            return
+        slora.lora_shrink_expand(dw.pool, 0, x_of(b, 0), wls[b].ids, wls[b].seg_offsets, ys[b][0].data_ptr(), stream)
+
+    def timed_calls(fn, n):
+        for i in range(2 * R):
+            fn(i % R)
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        for i in range(n):
+            fn(i % R)
+        t_b = time.perf_counter()
+        torch.cuda.synchronize()
+        t_c = time.perf_counter()
+        return (t_c - t_a) * 1e3 / n, (t_b - t_a) * 1e3 / n
+
+    n_cyc = max(R, min(args.steps, 64))
+    cyc_ms, cyc_host_ms = timed_calls(cycle, n_cyc)
+    shot_ms, shot_host_ms = timed_calls(one_shot, n_cyc) if not args.y16 else (None, None)
+    stats_a = slora.pool_stats(dw.pool)
+    timed_calls(cycle, R)
+    stats_b = slora.pool_stats(dw.pool)
+
     cold_med, cold_min = per_step_ms(list(range(R)), max(R, min(args.steps, 64)))
     per_step_ms([0], 8)
     warm_med, warm_min = per_step_ms([0], 32)       # the same batch again and again: caches help
+    # what two dependent, near-empty launches cost on this stream (one-element torch kernels, back
+    # to back like the steps): the floor under a step made of a shrink and an expand launch
+    tiny = torch.zeros(1, device=dev)
+    with torch.cuda.stream(stream):
+        for _ in range(20):
+            tiny.add_(1.0)
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record(stream)
+        for _ in range(200):
+            tiny.add_(1.0)
+            tiny.add_(1.0)
+        f1.record(stream)
+    torch.cuda.synchronize()
+    launch_floor_us = f0.elapsed_time(f1) * 1e3 / 200
     tok_per_step = float(np.mean([w.T for w in wls]))
     bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
     t_act_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H for w in wls]))
@@ -218,11 +269,15 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     dom_gbs = ex_gbs if dom == "expand" else sh_gbs
     kinds = ("mfma" if info["groups_mfma"] and not info["groups_vec"] else
              "vec" if not info["groups_mfma"] else "vec+mfma")
+    traffic = ({} if args.y16 or args.shared_x or args.opt else
+               MEASURED_TRAFFIC.get((w0.name, args.law, args.mode, R), {}))
     roofline = {
         "bound": "hbm", "kernel": f"{dom}_{kinds}", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
-        "traffic": (None if args.y16 or args.shared_x or args.opt else
-                    MEASURED_TRAFFIC.get((w0.name, args.law, args.mode, R), {}).get(f"{dom}_{kinds}")),
+        "traffic": traffic.get(f"{dom}_{kinds}"),
+        "traffic_source": (None if not traffic else
+                           f"{traffic['source']} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
+                           "line, taken earlier: counters cannot be read inside a timed run)"),
         "algorithmic_bytes_per_launch": int((ex_b if dom == "expand" else sh_b) * min(n_slots, slora.MAX_MULTI)),
         "avg_launch_us": round((ex_t if dom == "expand" else sh_t) * 1e6, 2),
         "other_kernel": {"kernel": f"{'shrink' if dom == 'expand' else 'expand'}_{kinds}",
@@ -231,27 +286,45 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "slots_per_launch": min(n_slots, slora.MAX_MULTI),
     }
 
-    # ---- check the timed path against the oracle, and time the oracle as it stands -------------
-    cpu = None
-    if not no_cpu:
-        from oracle import c_oracle
-        w = w0
-        real_slots = dw.real_slots
-        packs = [(s, w.compact_pool(s), w.x_bits(s), w.y_in(s)) for s in real_slots]
-        # parity of the timed path on batch 0, every slot that holds seeded weights
-        rel = mx = 0.0
-        cores = 1
-        for s, (rows, lists), xb, yb in packs:
-            ref, cores = c_oracle.lora_apply(rows, w.dtype, lists, w.ids, xb, yb, return_threads=True)
-            xg = bits_to_device(xb, dev)
-            yg = torch.from_numpy(yb).to(dev)
-            slora.lora_apply(plans[0], s, xg.data_ptr(), yg.data_ptr(), stream)
-            torch.cuda.synchronize()
-            got = yg.cpu().numpy().astype(np.float64)
+    # ---- parity of the timed launch shape: batch 0, EVERY slot, against the oracle -----------------
+    # The GPU side is the call the timed loop makes (all slots, up to 8 per launch pair, on the
+    # plan of batch 0) on fresh y buffers.  The oracle computes a seeded sample of the tokens one
+    # by one (all of them when the batch is small); sampled rows are compared element by element.
+    from oracle import c_oracle
+    w = w0
+    act = np.nonzero(w.ids >= 0)[0]
+    n_samp = int(min(act.size, args.parity_tokens))
+    samp = np.sort(np.random.default_rng(w.seed).choice(act, size=n_samp, replace=False)) if n_samp else act
+    ids_s = np.full_like(w.ids, -1)
+    ids_s[samp] = w.ids[samp]
+    samp_d = torch.from_numpy(samp).to(dev)
+    rel = mx = 0.0
+    for g0 in range(0, n_slots, slora.MAX_MULTI):
+        grp = slots[g0:g0 + slora.MAX_MULTI]
+        yg = [torch.from_numpy(w.y_in(s % 4)).to(dev) for s in grp]
+        slora.lora_apply_multi(plans[0], grp, [x_of(0, s) for s in grp], [t.data_ptr() for t in yg], stream)
+        torch.cuda.synchronize()
+        for s, t in zip(grp, yg):
+            if not n_samp:
+                continue
+            rows, lists = w.compact_pool(s, np.unique(ids_s[samp]))
+            xb = w.x_bits((3 if s % 4 == 3 else 0) if args.shared_x else s % 4)
+            ref = c_oracle.lora_apply(rows, w.dtype, lists, ids_s, xb, w.y_in(s % 4))[samp]
+            got = t[samp_d].cpu().numpy().astype(np.float64)
             rel = max(rel, float(np.linalg.norm(got - ref) / np.linalg.norm(ref)))
             mx = max(mx, float(np.abs(got - ref).max()))
-        if not (rel <= 1e-3 and mx <= 1e-2):
-            raise RuntimeError(f"GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})")
+        del yg
+    parity = {"slots_checked": n_slots, "tokens_checked_per_slot": n_samp, "of_tokens": int(act.size),
+              "rel_l2": rel, "max_abs": mx, "bars": {"rel_l2": 1e-3, "max_abs": 1e-2}}
+    if not (np.isfinite(rel) and rel <= 1e-3 and mx <= 1e-2):
+        raise RuntimeError(f"GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})")
+
+    # ---- the oracle as it stands, timed on this machine's host cores ---------------------------------
+    cpu = None
+    if not no_cpu:
+        packs = [(s, w.compact_pool(s), w.x_bits(s), w.y_in(s)) for s in range(min(n_slots, 4))]
+        _, cores = c_oracle.lora_apply(packs[0][1][0], w.dtype, packs[0][1][1], w.ids[:1], packs[0][2][:1],
+                                       packs[0][3][:1], return_threads=True)
         # timing: whole passes (all tokens of batch 0 x the seeded slots) until ~cpu_seconds of
         # summed core time have been spent
         passes, t_cpu = 0, 0.0
@@ -272,10 +345,10 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                "kind": "oracle",
                "sample": f"{passes} pass(es) over the {w.T} tokens of batch 0 x {len(packs)} slot(s): "
                          f"{t_cpu:.2f}s wall on {cores} threads, scaled to the {n_slots} slots a token "
-                         "passes per step",
+                         "passes per step; the oracle reads a compact re-paging of the adapters batch 0 "
+                         "uses (same weights, pages renumbered), not the full-size pool",
                "value_1_thread": round(k1 / t_one / n_slots, 2),
-               "sample_1_thread": f"{k1} tokens x 1 slot in {t_one:.2f}s on 1 thread, scaled the same way",
-               "gpu_vs_oracle_rel_l2": rel, "gpu_vs_oracle_max_abs": mx}
+               "sample_1_thread": f"{k1} tokens x 1 slot in {t_one:.2f}s on 1 thread, scaled the same way"}
 
     fetch = None
     if args.fetch:
@@ -362,7 +435,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
     roofline["frac_of_measured_copy"] = round(dom_gbs / copy_gbs, 4)
 
     ablation = None
-    if args.ablation:
+    plain = args.mode == "fused" and not (args.y16 or args.graph or args.shared_x or args.opt)
+    if args.ablation == "on" or (args.ablation == "auto" and plain and workload in (3, 4)):
         # (1) the padded batched-matmul formulation the paper compares its kernels with
         #     (Sec. 7.1, "bmm"): gather every token's adapter from the pool into contiguous
         #     tensors padded to the largest rank, then two torch.bmm calls; (2) the base
@@ -406,6 +480,17 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
             torch.cuda.synchronize()
             return a.elapsed_time(b) / reps
 
+        # the two formulations against each other on the same fresh y (the delta they add)
+        y_in0 = torch.from_numpy(w0.y_in(0)).to(dev)
+        with torch.cuda.stream(stream):
+            y32.copy_(y_in0)
+            bmm_step()
+            d_bmm = (y32 - y_in0).double()
+            y_k = y_in0.clone()
+            slora.lora_apply(plans[0], 0, x_of(0, 0), y_k.data_ptr(), stream)
+            d_ker = (y_k - y_in0).double()
+            bmm_vs_kernels = float((d_bmm - d_ker).norm() / d_ker.norm())
+        del y_in0, y_k, d_bmm, d_ker
         t_bmm = time_on(stream, bmm_step, 5)
         one_slot = lambda: apply_one(plans[0], 0, x_of(0, 0), ys[0][0].data_ptr(), stream)
         t_ours = time_on(stream, one_slot, 20)
@@ -431,6 +516,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         t_both = max(a0.elapsed_time(a1), a0.elapsed_time(g1)) / 20
         ablation = {"padded_bmm_ms_per_slot": round(t_bmm, 4), "lora_kernels_ms_per_slot": round(t_ours, 4),
                     "padded_bmm_rank": rmax, "speedup_over_padded_bmm": round(t_bmm / t_ours, 2),
+                    # the bmm's v and output are rounded to the 16-bit type: agreement to ~1e-3
+                    "padded_bmm_vs_lora_kernels_rel_l2_of_delta": bmm_vs_kernels,
                     "base_gemm_ms_per_step": round(t_gemm, 4), "lora_ms_per_step": round(t_step, 4),
                     "both_streams_ms_per_step": round(t_both, 4),
                     "serial_ms_per_step": round(t_gemm + t_step, 4)}
@@ -447,15 +534,25 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                    "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
         "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
         "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+        "hbm_frac_median_step": round(bytes_step / (cold_med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "mfma_util": round(flops_step / (wall / args.steps) / 1e12 / MFMA_PEAK_TFLOPS, 5),
+        # the most the matrix cores can be busy while HBM keeps up: arithmetic intensity x 8 TB/s
+        "mfma_util_cap": round(flops_step / bytes_step * HBM_PEAK_GBS * 1e9 / (MFMA_PEAK_TFLOPS * 1e12), 5),
         "algorithmic_bytes_per_step": int(bytes_step), "flops_per_step": int(flops_step),
         "event_ms_per_step": round(ev_ms / args.steps, 5),
         "step_ms_median": round(cold_med, 5), "step_ms_min": round(cold_min, 5),
         "warm_step_ms_median": round(warm_med, 5), "warm_step_ms_min": round(warm_min, 5),
         "plan_ms": round(float(np.median(plan_s)) * 1e3, 4),
-        "ms_per_step_with_plan": round(ms_per_step + float(np.median(plan_s)) * 1e3, 5),
+        # a new plan every step: plan + apply of all slots + plan_destroy, pipelined (wall per
+        # cycle with the final synchronisation; host = until the cycle's calls have returned)
+        "plan_lifecycle_ms": round(cyc_ms, 5), "plan_lifecycle_host_ms": round(cyc_host_ms, 5),
+        "plan_lifecycle_over_apply_ms": round(cyc_ms - ms_per_step, 5),
+        "one_shot_ms": None if shot_ms is None else round(shot_ms, 5),
+        "one_shot_host_ms": None if shot_ms is None else round(shot_host_ms, 5),
+        "allocations_in_steady_cycles": stats_b["allocations"] - stats_a["allocations"],
+        "launch_floor_us": round(launch_floor_us, 2),
         "naive_bytes_per_step": int(naive_step),
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
     if fetch:
         out["fetch"] = fetch
@@ -474,9 +571,10 @@ def main() -> int:
     ap.add_argument("--law", default="power", choices=["power", "zipf"])
     ap.add_argument("--batches", type=int, default=8, help="distinct batches the steps rotate over")
     ap.add_argument("--mode", default="fused", choices=["fused", "qkv_o", "per_slot"])
-    ap.add_argument("--ablation", action="store_true",
+    ap.add_argument("--ablation", default="auto", choices=["auto", "on", "off"],
                     help="also time the padded torch.bmm formulation of one slot and the base projection "
-                         "x W running on a second stream beside the LoRA step")
+                         "x W running on a second stream beside the LoRA step (auto: for the plain fused runs "
+                         "of workloads 3 and 4)")
     ap.add_argument("--fetch", type=int, default=0,
                     help="also time the upload of this many rank-64 adapters from pinned host memory on a side "
                          "stream, alone and while the steps run")
@@ -488,7 +586,9 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true", help="replay the steps as one HIP graph per rotation")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="core-seconds of oracle work to time")
-    ap.add_argument("--also", default="2,3", help="workloads whose summary is nested under 'also' when the "
+    ap.add_argument("--parity-tokens", type=int, default=32,
+                    help="tokens per slot of batch 0 the oracle recomputes for the in-run parity check")
+    ap.add_argument("--also", default="2,3,5", help="workloads whose summary is nested under 'also' when the "
                     "primary one is config 4 (comma list, 'none' to skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -500,11 +600,13 @@ def main() -> int:
         out = measure(args, args.workload, args.no_cpu)
         if args.workload == 4 and args.also != "none":
             keep = ("value", "unit", "ms_per_step", "step_ms_median", "step_ms_min", "warm_step_ms_median",
-                    "plan_ms", "hbm_gbps", "hbm_frac", "mfma_util", "config", "roofline")
+                    "plan_ms", "plan_lifecycle_ms", "one_shot_ms", "launch_floor_us", "hbm_gbps", "hbm_frac",
+                    "hbm_frac_median_step", "mfma_util", "mfma_util_cap", "config", "roofline", "ablation",
+                    "parity")
             out["also"] = []
             for n in (int(v) for v in args.also.split(",")):
                 o = measure(args, n, True)
-                out["also"].append({k: o[k] for k in keep})
+                out["also"].append({k: o[k] for k in keep if k in o})
     except RuntimeError as e:
         print(f"bench.py: {e}", file=sys.stderr)
         return 1

@@ -27,7 +27,11 @@
  *   - Page j of an adapter's A list holds column j of A (an H-vector), page j of its B list
  *     holds row j of B.  All projections map H -> H.
  *   - The pool memory is borrowed from the caller and never allocated, freed or cleared here.
- *     The library allocates (hipMalloc) only its own tables, work lists and the v scratch.
+ *     The library allocates only its own tables, work lists, staging buffers and the v scratch,
+ *     and recycles them: a steady sequence of plan / apply / destroy (Sec. 4.1 forms a new batch
+ *     every iteration) allocates nothing after the first few batches and never waits for the
+ *     device.
+ *   - Every call leaves the caller's current HIP device as it found it.
  *   - A handle must not be used from two threads at once.
  */
 #ifndef SLORA_H
@@ -70,27 +74,49 @@ const char *slora_last_error(void);
 int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32_t dtype,
                         void *dev_base, int32_t n_slots, int32_t max_rank);
 
-/* Frees the library's tables.  Plans made from the pool must be destroyed first (EBUSY). */
+/*
+ * Frees the library's tables and recycled buffers after waiting for the device to go idle.
+ * Plans made from the pool must be destroyed first (EBUSY).
+ */
 int32_t slora_pool_destroy(slora_pool *pool);
 
 /*
+ * Allocation statistics, for tests and tuning: fills out[0..n) (n <= SLORA_POOL_STATS_N) with
+ *  [0] buffer sets (pinned image + device image + v scratch) ever created for plans, page
+ *      writes and page-list uploads   [1] device / pinned allocations made for them and for
+ *      the page-list image            [2] sets waiting to be handed out again.
+ * [0] and [1] stop growing once the caller's mix of batch sizes has been seen.
+ */
+#define SLORA_POOL_STATS_N 3
+int32_t slora_pool_stats(const slora_pool *pool, int64_t *out, int32_t n);
+
+/*
  * Mark pages as holding KV cache (owned != 0) or release them (owned == 0).  page_idx: HOST.
+ * Sec. 5.1, Fig. 3: KV-cache vectors and adapter weights are interleaved in one pool of
+ * H-vector pages.
  * KV pages can never be given to an adapter; the LoRA kernels never read or write them.
  * Errors: ERANGE (index), EBUSY (page owned by an adapter, or listed twice).
  */
 int32_t slora_pool_mark_kv(slora_pool *pool, const int32_t *page_idx, int64_t n, int32_t owned);
 
 /*
- * Copy n H-vectors into the named pages: pool[page_idx[i]] = src[i*H .. (i+1)*H).
- * page_idx: HOST.  src: HOST if src_on_device == 0, else DEVICE, in the pool's storage type.
- * Returns after the copy has completed on `stream`.  Ownership is not consulted (the caller
- * also writes KV pages); only the index range is checked (ERANGE).
+ * Copy n H-vectors into the named pages: pool[page_idx[i]] = src[i*H .. (i+1)*H) (Sec. 5.1: a
+ * page holds one vector of H elements, for KV cache and adapter weights alike; Sec. 5.2: adapters
+ * are brought from host memory into pool pages).
+ * page_idx: HOST.  src: HOST (pageable or pinned) if src_on_device == 0, else DEVICE, 16-byte
+ * aligned, in the pool's storage type.  Asynchronous on `stream`: page_idx and a HOST src are
+ * copied into a recycled pinned buffer before the call returns (so they may be reused at once);
+ * a DEVICE src is read by a kernel on `stream` and must stay valid until the stream has run
+ * it.  Ownership is not consulted (the caller also writes KV pages); only the index range is
+ * checked (ERANGE).
  */
 int32_t slora_pool_write_pages(slora_pool *pool, const int32_t *page_idx, int64_t n,
                                const void *src, int32_t src_on_device, void *stream);
 
 /*
- * Make adapter `adapter_id` (any id >= 0) resident with rank `rank`.  page_idx: HOST, n_idx =
+ * Make adapter `adapter_id` (any id >= 0) resident with rank `rank` (Sec. 5.1: a LoRA matrix of
+ * rank r takes r pages, placed anywhere in the pool; Sec. 2: one A (H x r) and one B (r x H)
+ * per adapted projection).  page_idx: HOST, n_idx =
  * n_slots*2*rank entries ordered [slot][A columns j=0..rank-1][B rows j=0..rank-1].  The
  * pages must already hold (or later receive, before the first apply) the weights.
  * rank 0 (n_idx 0) is legal: such an adapter contributes exactly nothing.
@@ -100,7 +126,12 @@ int32_t slora_pool_write_pages(slora_pool *pool, const int32_t *page_idx, int64_
 int32_t slora_adapter_load(slora_pool *pool, int32_t adapter_id, int32_t rank,
                            const int32_t *page_idx, int64_t n_idx);
 
-/* Release the adapter's pages (they become free).  Plans built earlier become stale. */
+/*
+ * Evict the adapter (Sec. 5.1 / 5.2: adapters of finished requests make room for KV cache or
+ * for other adapters): its pages become free.  Every plan built earlier becomes stale (EBUSY
+ * when applied).  Launches already enqueued that use the adapter keep reading its pages and
+ * page lists: the caller orders their completion before the pages are written again.
+ */
 int32_t slora_adapter_unload(slora_pool *pool, int32_t adapter_id);
 
 /*
@@ -135,7 +166,9 @@ int32_t slora_adapter_alloc(slora_pool *pool, int32_t adapter_id, int32_t rank, 
 int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *weights, void *stream);
 
 /*
- * Gather one paged matrix into contiguous DEVICE memory: dev_out[j*H + h] = page j of the A
+ * Gather one paged matrix into contiguous DEVICE memory (the inverse of the paged placement of
+ * Sec. 5.1, Fig. 3; what a padded batched-matmul formulation, Sec. 7.1, would have to do for
+ * every token): dev_out[j*H + h] = page j of the A
  * (which = 0) or B (which = 1) list of (adapter, slot); rank*H elements, bit-exact copies.
  */
 int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot, int32_t which,
@@ -152,9 +185,21 @@ int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot,
  * matrix-vector kernels and large ones (when the batch has enough of them) to the MFMA
  * kernels, and can be applied to any slot, any number of times, until an adapter is unloaded.
  * T == 0 is legal.
+ * The work lists travel to the device asynchronously on a stream the pool owns, together with
+ * the page lists of adapters loaded since the previous plan; the first launch of the plan waits
+ * for that copy through an event, on the device.  No host-side wait, and no allocation once
+ * recycled buffers of sufficient size exist.
  */
 int32_t slora_batch_plan(slora_pool *pool, slora_plan **out, const int32_t *token_adapter_ids,
                          int32_t T, const int32_t *seg_offsets, int32_t n_seg);
+
+/*
+ * End of a batch (Sec. 4.1: the batch changes every iteration).  Never waits and never frees:
+ * the plan's device buffers return to the pool behind an event recorded on the stream of the
+ * plan's last launch and are reused by a later plan once that event has completed.  Work the
+ * plan has enqueued runs to completion as if the plan still existed.  HIP graphs that captured
+ * applies of the plan must not be replayed afterwards.
+ */
 int32_t slora_plan_destroy(slora_plan *plan);
 
 /*
@@ -173,9 +218,14 @@ int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n);
  * row-major, updated in place.  Asynchronous on `stream`; x and y must stay valid until the
  * stream has run the work.  Rows of tokens with id -1 or a rank-0 adapter are not accessed.
  * Results are deterministic: no floating-point atomics, fixed reduction order per plan.
- * Once a plan has been applied with n slots, further applies with at most n slots allocate
- * nothing and may be captured in a HIP graph; a replay stays valid until an adapter the plan
- * uses is unloaded (the host-side checks of this call are not part of the graph).
+ * All launches of one plan share its work lists and its v scratch and therefore run in ONE
+ * order: a call that names another stream than the plan's previous call makes the new stream
+ * wait (on the device, through an event) for the work enqueued before.  To run projections
+ * concurrently on several streams, give each stream its own plan.
+ * Once a plan has been applied with n slots on a stream, further applies with at most n slots
+ * on that stream allocate nothing, touch no event, and may be captured in a HIP graph; a
+ * replay stays valid until the plan is destroyed or an adapter it uses is unloaded (the
+ * host-side checks of this call are not part of the graph).
  */
 int32_t slora_lora_apply(slora_plan *plan, int32_t slot, const void *x, float *y, void *stream);
 
@@ -189,9 +239,10 @@ int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots
                                const void *const *x, float *const *y, void *stream);
 
 /*
- * The two stages on their own (the paper's kernels are a shrink x*A followed by an expand
- * v*B).  shrink writes v = x*A_i into the plan's scratch; expand adds v*B_i onto y.  An expand
- * uses the v left by the latest shrink on the same plan with the same n.
+ * The two stages of Eq. 2 on their own (Sec. 5.3: the custom kernels compute x*A and then
+ * (x*A)*B, gathering the weights from non-contiguous pool pages without padding).  shrink
+ * writes v[t,:] = x[t,:] * A_i into the plan's scratch; expand adds v[t,:] * B_i onto y[t,:].
+ * An expand uses the v left by the latest shrink on the same plan with the same n.
  */
 int32_t slora_lora_shrink(slora_plan *plan, int32_t n, const int32_t *slots,
                           const void *const *x, void *stream);
@@ -213,7 +264,14 @@ int32_t slora_lora_apply_multi_y16(slora_plan *plan, int32_t n, const int32_t *s
 int32_t slora_lora_expand_y16(slora_plan *plan, int32_t n, const int32_t *slots,
                               void *const *y, void *stream);
 
-/* One-shot form: plan + apply(slot) + plan_destroy; returns after the work has completed. */
+/*
+ * One-shot form of Eq. 2 for a batch described by its adapter ids and request segments (Sec.
+ * 4.1): plan + apply(slot) + plan_destroy.  Arguments as for slora_batch_plan and
+ * slora_lora_apply.  Asynchronous on `stream` like slora_lora_apply (the host arrays are fully
+ * read before return); it does not wait for the device and, in the steady state, allocates
+ * nothing.  A caller with several projections or layers per batch saves the scheduling work by
+ * keeping one plan for all of them.
+ */
 int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
                                  const int32_t *token_adapter_ids, const int32_t *seg_offsets,
                                  int32_t n_seg, int32_t T, float *y, void *stream);

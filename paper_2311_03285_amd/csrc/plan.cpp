@@ -214,14 +214,14 @@ int32_t slora_plan::upload()
     if (n_tok == 0) return SLORA_OK;
     const size_t tok_bytes = (n_tok * sizeof(int32_t) + 31) / 32 * 32;
     const size_t bytes = tok_bytes + n_items * sizeof(Item);
-    std::vector<unsigned char> img;
-    try {
-        img.resize(bytes);
-    } catch (const std::bad_alloc &) {
-        return fail(SLORA_ENOMEM, "out of host memory while planning");
-    }
-    std::memcpy(img.data(), tok_idx.data(), n_tok * sizeof(int32_t));
-    unsigned char *at = img.data() + tok_bytes;
+    // The image is assembled in the pinned half of a recycled buffer set and copied to the
+    // device half on the pool's own upload stream: the copy runs beside whatever the caller's
+    // streams are doing, and the first launch of the plan waits for it through an event.
+    int32_t rc = pool->take_set(&set, bytes, bytes);
+    if (rc != SLORA_OK) return rc;
+    unsigned char *img = static_cast<unsigned char *>(set->h);
+    std::memcpy(img, tok_idx.data(), n_tok * sizeof(int32_t));
+    unsigned char *at = img + tok_bytes;
     auto put = [&](const std::vector<Item> &v) {
         if (!v.empty()) std::memcpy(at, v.data(), v.size() * sizeof(Item));
         at += v.size() * sizeof(Item);
@@ -230,43 +230,41 @@ int32_t slora_plan::upload()
     put(ve_items);
     put(ms_items);
     put(me_items);
-    hipError_t e = hipSetDevice(pool->device);
-    if (e == hipSuccess) e = hipMalloc(&d_blob, bytes);
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(plan)");
-    e = hipMemcpy(d_blob, img.data(), bytes, hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-        (void)hipFree(d_blob);
-        d_blob = nullptr;
-        return hip_fail(e, "hipMemcpy(plan)");
+    void *up_v = nullptr;
+    rc = pool->uploads(&up_v);
+    if (rc != SLORA_OK) {
+        pool->give_set(set, nullptr);
+        set = nullptr;
+        return rc;
     }
-    d_tok_idx = (int32_t *)d_blob;
-    d_vs = (Item *)((unsigned char *)d_blob + tok_bytes);
+    hipStream_t up = (hipStream_t)up_v;
+    hipError_t e = hipMemcpyAsync(set->d, set->h, bytes, hipMemcpyHostToDevice, up);
+    if (e == hipSuccess) e = hipEventRecord((hipEvent_t)set->order, up);
+    if (e != hipSuccess) {
+        rc = hip_fail(e, "uploading the work lists");
+        pool->give_set(set, pool->upload_stream);
+        set = nullptr;
+        return rc;
+    }
+    last_stream = pool->upload_stream;
+    order_recorded = true;
+    d_tok_idx = (int32_t *)set->d;
+    d_vs = (Item *)((unsigned char *)set->d + tok_bytes);
     d_ve = d_vs + vs_items.size();
     d_ms = d_ve + ve_items.size();
     d_me = d_ms + ms_items.size();
     return SLORA_OK;
 }
 
-int32_t slora_plan::ensure_v(int32_t n)
+int32_t slora_plan::enter(void *stream)
 {
-    const int64_t need = (int64_t)n * v_slot_floats(pool->dtype);
-    if (need <= d_v_cap) return SLORA_OK;
-    // Launches in flight and applies captured in a HIP graph hold the old scratch's address: it
-    // stays allocated until the plan is destroyed (a call with more slots than any before is rare).
-    float *fresh = nullptr;
-    hipError_t e = hipMalloc((void **)&fresh, (size_t)need * sizeof(float));
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(v scratch)");
-    if (d_v) {
-        try {
-            retired_v.push_back(d_v);
-        } catch (const std::bad_alloc &) {
-            (void)hipFree(fresh);
-            return fail(SLORA_ENOMEM, "out of host memory");
-        }
-    }
-    d_v = fresh;
-    d_v_cap = need;
-    v_slots = 0; // the new scratch holds no shrink result yet
+    if (!set || stream == last_stream) return SLORA_OK;
+    hipError_t e = hipSuccess;
+    if (!order_recorded) e = hipEventRecord((hipEvent_t)set->order, (hipStream_t)last_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)set->order, 0);
+    if (e != hipSuccess) return hip_fail(e, "ordering the plan's work between two streams");
+    last_stream = stream;
+    order_recorded = false;
     return SLORA_OK;
 }
 
@@ -286,7 +284,9 @@ int32_t check_plan(slora_plan *plan, int32_t n, const int32_t *slots)
     return SLORA_OK;
 }
 
-int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *stream)
+// scratch: where v goes; NULL = the plan's own buffer (grown on demand)
+int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *stream,
+                  float *scratch = nullptr)
 {
     if (!x) return fail(SLORA_EINVAL, "x is NULL");
     if (plan->T_act == 0) return SLORA_OK;
@@ -298,17 +298,25 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
         a.x[k] = x[k];
         a.slot[k] = slots[k];
     }
-    int32_t rc = plan->pool->sync_device();
-    if (rc == SLORA_OK) {
-        hipError_t e = hipSetDevice(plan->pool->device);
-        if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
-        rc = plan->ensure_v(n);
+    DeviceScope dev(plan->pool->device);
+    if (dev.status() != SLORA_OK) return dev.status();
+    // the page lists of every adapter the plan names went to the device when it was built
+    const int64_t need = (int64_t)n * plan->v_slot_floats(plan->pool->dtype);
+    float *v = scratch;
+    int32_t rc = SLORA_OK;
+    if (!v) {
+        rc = plan->pool->grow_v(plan->set, (size_t)need);
+        v = plan->set->v;
     }
+    if (rc == SLORA_OK) rc = plan->enter(stream);
     if (rc != SLORA_OK) return rc;
-    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
+    for (int32_t k = 0; k < n; ++k) a.v[k] = v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
     a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
     rc = launch_shrink(plan, n, a, stream);
-    if (rc == SLORA_OK) plan->v_slots = n;
+    if (rc == SLORA_OK) {
+        plan->v_slots = n;
+        plan->v_used = v;
+    }
     return rc;
 }
 
@@ -335,11 +343,13 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const
         a.y[k] = y[k];
         a.slot[k] = slots[k];
     }
-    if (plan->v_slots != n || !plan->d_v)
+    if (plan->v_slots != n || !plan->v_used)
         return fail(SLORA_EINVAL, "expand of %d slot(s) needs a preceding shrink of %d slot(s)", n, n);
-    hipError_t e = hipSetDevice(plan->pool->device);
-    if (e != hipSuccess) return hip_fail(e, "hipSetDevice");
-    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->d_v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
+    DeviceScope dev(plan->pool->device);
+    if (dev.status() != SLORA_OK) return dev.status();
+    rc = plan->enter(stream);
+    if (rc != SLORA_OK) return rc;
+    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->v_used + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
     a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
     return launch_expand(plan, n, a, stream, y16);
 }
@@ -359,7 +369,13 @@ int32_t slora_batch_plan(slora_pool *pool, slora_plan **out, const int32_t *toke
     p->pool = pool;
     p->generation = pool->unload_generation;
     int32_t rc = build_plan(pool, p, token_adapter_ids, T, seg_offsets, n_seg);
-    if (rc == SLORA_OK) rc = p->upload();
+    if (rc == SLORA_OK && pool->dev_base) {
+        DeviceScope dev(pool->device);
+        rc = dev.status();
+        // page lists of adapters loaded since the last plan, then this plan's work lists
+        if (rc == SLORA_OK) rc = pool->sync_device();
+        if (rc == SLORA_OK) rc = p->upload();
+    }
     if (rc != SLORA_OK) {
         delete p;
         return rc;
@@ -373,12 +389,12 @@ int32_t slora_plan_destroy(slora_plan *plan)
 {
     clear_error();
     if (!plan) return SLORA_OK;
-    if (plan->d_blob || plan->d_v) {
-        (void)hipSetDevice(plan->pool->device);
-        (void)hipDeviceSynchronize();
-        if (plan->d_blob) (void)hipFree(plan->d_blob);
-        if (plan->d_v) (void)hipFree(plan->d_v);
-        for (float *old_v : plan->retired_v) (void)hipFree(old_v);
+    if (plan->set) {
+        // Nothing is freed and nothing is waited for: the buffers go back to the pool with an
+        // event recorded behind the plan's last launch and are handed out again after it.
+        DeviceScope dev(plan->pool->device);
+        plan->pool->give_set(plan->set, plan->last_stream);
+        plan->set = nullptr;
     }
     plan->pool->live_plans--;
     delete plan;
@@ -471,14 +487,7 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x, 
     if (rc != SLORA_OK) return rc;
     rc = slora_lora_apply(plan, slot, x, y, stream);
     std::string keep = last_error_cstr();
-    if (rc == SLORA_OK) {
-        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
-        if (e != hipSuccess) {
-            rc = hip_fail(e, "hipStreamSynchronize");
-            keep = last_error_cstr();
-        }
-    }
-    (void)slora_plan_destroy(plan);
+    (void)slora_plan_destroy(plan); // the plan's buffers are recycled after the launches have run
     if (rc != SLORA_OK) fail(rc, "%s", keep.c_str());
     return rc;
 }

@@ -31,6 +31,21 @@ static int32_t hip_fail(hipError_t e, const char *what)
     return fail(SLORA_EHIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+DeviceScope::DeviceScope(int device)
+{
+    if (device < 0) return; // host-only pool: no HIP call at all
+    hipError_t e = hipGetDevice(&prev_);
+    if (e == hipSuccess && prev_ != device) {
+        e = hipSetDevice(device);
+        switched_ = e == hipSuccess;
+    }
+    if (e != hipSuccess) rc_ = hip_fail(e, "selecting the pool's device");
+}
+DeviceScope::~DeviceScope()
+{
+    if (switched_) (void)hipSetDevice(prev_);
+}
+
 } // namespace slora
 
 using namespace slora;
@@ -41,17 +56,166 @@ using namespace slora;
         if (e_ != hipSuccess) return hip_fail(e_, #expr); \
     } while (0)
 
+// ---------------------------------------------------------------------------------------
+// recycled buffer sets
+// ---------------------------------------------------------------------------------------
+namespace {
+size_t round_up_pow2(size_t n, size_t floor)
+{
+    size_t c = floor;
+    while (c < n) c *= 2;
+    return c;
+}
+} // namespace
+
+int32_t slora_pool::take_set(Buffers **out, size_t h_bytes, size_t d_bytes)
+{
+    *out = nullptr;
+    Buffers *set = nullptr;
+    // newest first: the set parked last is the most likely to be large enough
+    for (size_t k = idle_sets.size(); k-- > 0;) {
+        Buffers *c = idle_sets[k];
+        const hipError_t q = hipEventQuery((hipEvent_t)c->order);
+        if (q == hipErrorNotReady) {
+            (void)hipGetLastError();
+            continue; // its last user's work is still running: leave it parked
+        }
+        if (q != hipSuccess) return hip_fail(q, "hipEventQuery");
+        set = c;
+        idle_sets.erase(idle_sets.begin() + (ptrdiff_t)k);
+        break;
+    }
+    if (!set) {
+        set = new (std::nothrow) Buffers;
+        if (!set) return fail(SLORA_ENOMEM, "out of host memory");
+        hipEvent_t ev = nullptr;
+        hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            delete set;
+            return hip_fail(e, "hipEventCreate");
+        }
+        set->order = ev;
+        sets_made++;
+    }
+    // grow what is too small; nothing that ran on this set is still in flight, so the old
+    // buffers can go at once (capacities double: a steady mix of batch sizes stops growing)
+    hipError_t e = hipSuccess;
+    if (set->h_cap < h_bytes) {
+        if (set->h) (void)hipHostFree(set->h);
+        set->h = nullptr;
+        set->h_cap = 0;
+        const size_t cap = round_up_pow2(h_bytes, 1 << 16);
+        e = hipHostMalloc(&set->h, cap, hipHostMallocDefault);
+        if (e == hipSuccess) set->h_cap = cap, device_allocs++;
+    }
+    if (e == hipSuccess && set->d_cap < d_bytes) {
+        if (set->d) (void)hipFree(set->d);
+        set->d = nullptr;
+        set->d_cap = 0;
+        const size_t cap = round_up_pow2(d_bytes, 1 << 16);
+        e = hipMalloc(&set->d, cap);
+        if (e == hipSuccess) set->d_cap = cap, device_allocs++;
+    }
+    if (e == hipSuccess && !set->outgrown.empty()) {
+        for (void *p : set->outgrown) (void)hipFree(p);
+        set->outgrown.clear();
+    }
+    if (e != hipSuccess) {
+        idle_sets.push_back(set); // still consistent (event complete, buffers null or valid)
+        return hip_fail(e, "allocating a buffer set");
+    }
+    *out = set;
+    return SLORA_OK;
+}
+
+void slora_pool::give_set(Buffers *set, void *last_stream)
+{
+    if (!set) return;
+    // the set may be handed out again once everything enqueued so far on its last stream has run
+    (void)hipEventRecord((hipEvent_t)set->order, (hipStream_t)last_stream);
+    try {
+        idle_sets.push_back(set);
+    } catch (const std::bad_alloc &) { // cannot park it: wait and release it instead
+        (void)hipEventSynchronize((hipEvent_t)set->order);
+        if (set->h) (void)hipHostFree(set->h);
+        if (set->d) (void)hipFree(set->d);
+        if (set->v) (void)hipFree(set->v);
+        for (void *p : set->outgrown) (void)hipFree(p);
+        (void)hipEventDestroy((hipEvent_t)set->order);
+        delete set;
+    }
+}
+
+int32_t slora_pool::grow_v(Buffers *set, size_t floats)
+{
+    if (floats <= set->v_cap) return SLORA_OK;
+    const size_t cap = round_up_pow2(floats, 1 << 14);
+    float *fresh = nullptr;
+    hipError_t e = hipMalloc((void **)&fresh, cap * sizeof(float));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(v scratch)");
+    device_allocs++;
+    if (set->v) {
+        // launches in flight, and applies captured in a HIP graph, still name the old scratch: it
+        // is released when the set is next handed out (after its event) or with the pool
+        try {
+            set->outgrown.push_back(set->v);
+        } catch (const std::bad_alloc &) {
+            (void)hipFree(fresh);
+            return fail(SLORA_ENOMEM, "out of host memory");
+        }
+    }
+    set->v = fresh;
+    set->v_cap = cap;
+    return SLORA_OK;
+}
+
+void slora_pool::free_sets()
+{
+    for (Buffers *set : idle_sets) {
+        if (set->h) (void)hipHostFree(set->h);
+        if (set->d) (void)hipFree(set->d);
+        if (set->v) (void)hipFree(set->v);
+        for (void *p : set->outgrown) (void)hipFree(p);
+        if (set->order) (void)hipEventDestroy((hipEvent_t)set->order);
+        delete set;
+    }
+    idle_sets.clear();
+    if (upload_stream) (void)hipStreamDestroy((hipStream_t)upload_stream);
+    upload_stream = nullptr;
+    if (arena_event) (void)hipEventDestroy((hipEvent_t)arena_event);
+    arena_event = nullptr;
+}
+
+int32_t slora_pool::uploads(void **out)
+{
+    if (!upload_stream) {
+        hipStream_t st = nullptr;
+        // default priority; non-blocking so that it never joins the legacy default stream
+        HIP_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+        upload_stream = st;
+    }
+    *out = upload_stream;
+    return SLORA_OK;
+}
+
+// Push the page lists that changed since the last call to the device image, asynchronously on
+// the upload stream (through a recycled pinned buffer); `arena_event` then marks the point
+// after which the image is complete.  Plans upload their work lists on the same stream
+// afterwards, so a plan's own event covers the lists too; other users wait for arena_event.
 int32_t slora_pool::sync_device()
 {
     if (!dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
     if (dirty_hi <= dirty_lo) return SLORA_OK;
-    HIP_TRY(hipSetDevice(device));
+    void *up = nullptr;
+    int32_t rc = uploads(&up);
+    if (rc != SLORA_OK) return rc;
     const int64_t need = (int64_t)arena.size();
     if (need > d_arena_cap) {
         int64_t cap = d_arena_cap ? d_arena_cap : 4096;
         while (cap < need) cap *= 2;
         int32_t *fresh = nullptr;
         HIP_TRY(hipMalloc((void **)&fresh, (size_t)cap * sizeof(int32_t)));
+        device_allocs++;
         if (d_arena) {
             // Kernels in flight, and applies captured in a HIP graph, hold the old image's address:
             // it stays allocated (and valid for every adapter loaded before this point) until
@@ -69,9 +233,28 @@ int32_t slora_pool::sync_device()
         dirty_lo = 0;
         dirty_hi = need;
     }
-    HIP_TRY(hipMemcpy(d_arena + dirty_lo, arena.data() + dirty_lo,
-                      (size_t)(dirty_hi - dirty_lo) * sizeof(int32_t), hipMemcpyHostToDevice));
+    const size_t bytes = (size_t)(dirty_hi - dirty_lo) * sizeof(int32_t);
+    Buffers *set = nullptr;
+    rc = take_set(&set, bytes, 0);
+    if (rc != SLORA_OK) return rc;
+    std::memcpy(set->h, arena.data() + dirty_lo, bytes);
+    hipError_t e = hipMemcpyAsync(d_arena + dirty_lo, set->h, bytes, hipMemcpyHostToDevice, (hipStream_t)up);
+    if (e == hipSuccess && !arena_event) {
+        hipEvent_t ev = nullptr;
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e == hipSuccess) arena_event = ev;
+    }
+    if (e == hipSuccess) e = hipEventRecord((hipEvent_t)arena_event, (hipStream_t)up);
+    give_set(set, up);
+    if (e != hipSuccess) return hip_fail(e, "uploading page lists");
     dirty_lo = dirty_hi = 0;
+    return SLORA_OK;
+}
+
+int32_t slora_pool::await_arena(void *stream)
+{
+    if (!arena_event) return SLORA_OK;
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)arena_event, 0));
     return SLORA_OK;
 }
 
@@ -195,13 +378,23 @@ int32_t slora_pool_destroy(slora_pool *pool)
     clear_error();
     if (!pool) return SLORA_OK;
     if (pool->live_plans) return fail(SLORA_EBUSY, "%lld plan(s) of this pool still exist", (long long)pool->live_plans);
-    if (pool->d_arena) {
-        (void)hipSetDevice(pool->device);
+    if (pool->dev_base) {
+        DeviceScope dev(pool->device);
         (void)hipDeviceSynchronize();
-        (void)hipFree(pool->d_arena);
+        if (pool->d_arena) (void)hipFree(pool->d_arena);
         for (int32_t *old_image : pool->retired_arenas) (void)hipFree(old_image);
+        pool->free_sets();
     }
     delete pool;
+    return SLORA_OK;
+}
+
+int32_t slora_pool_stats(const slora_pool *pool, int64_t *out, int32_t n)
+{
+    clear_error();
+    if (!pool || !out || n < 0 || n > SLORA_POOL_STATS_N) return fail(SLORA_EINVAL, "bad arguments");
+    const int64_t v[SLORA_POOL_STATS_N] = {pool->sets_made, pool->device_allocs, (int64_t)pool->idle_sets.size()};
+    for (int32_t k = 0; k < n; ++k) out[k] = v[k];
     return SLORA_OK;
 }
 
@@ -253,25 +446,26 @@ int32_t slora_pool_write_pages(slora_pool *pool, const int32_t *page_idx, int64_
                         (long long)pool->n_pages);
     if (!pool->dev_base) return fail(SLORA_EHIP, "pool is host-only (dev_base == NULL)");
     if (n == 0) return SLORA_OK;
-    HIP_TRY(hipSetDevice(pool->device));
+    DeviceScope dev(pool->device);
+    if (dev.status() != SLORA_OK) return dev.status();
     hipStream_t st = (hipStream_t)stream;
-    int32_t *d_idx = nullptr;
-    void *d_src = nullptr;
-    int32_t rc = SLORA_OK;
-    hipError_t e = hipMalloc((void **)&d_idx, (size_t)n * sizeof(int32_t));
-    if (e != hipSuccess) return hip_fail(e, "hipMalloc(page index list)");
-    e = hipMemcpyAsync(d_idx, page_idx, (size_t)n * sizeof(int32_t), hipMemcpyHostToDevice, st);
-    if (e == hipSuccess && !src_on_device) {
-        const size_t bytes = (size_t)n * pool->H * 2;
-        e = hipMalloc(&d_src, bytes);
-        if (e == hipSuccess) e = hipMemcpyAsync(d_src, src, bytes, hipMemcpyHostToDevice, st);
-    }
-    if (e != hipSuccess) rc = hip_fail(e, "staging pages");
-    if (rc == SLORA_OK) rc = launch_write_pages(pool, d_idx, n, src_on_device ? src : d_src, stream);
-    e = hipStreamSynchronize(st);
-    if (rc == SLORA_OK && e != hipSuccess) rc = hip_fail(e, "hipStreamSynchronize");
-    (void)hipFree(d_idx);
-    if (d_src) (void)hipFree(d_src);
+    // The index list (and host-side page data) is copied into a recycled pinned buffer, from
+    // there to the device with ONE asynchronous copy on `stream`, and scattered by a kernel on
+    // the same stream.  The caller's arrays are free again when this call returns; the set goes
+    // back to the pool and is reused after the kernel has run.
+    const size_t idx_bytes = ((size_t)n * sizeof(int32_t) + 255) / 256 * 256;
+    const size_t src_bytes = src_on_device ? 0 : (size_t)n * pool->H * 2;
+    Buffers *set = nullptr;
+    int32_t rc = pool->take_set(&set, idx_bytes + src_bytes, idx_bytes + src_bytes);
+    if (rc != SLORA_OK) return rc;
+    std::memcpy(set->h, page_idx, (size_t)n * sizeof(int32_t));
+    if (src_bytes) std::memcpy(static_cast<unsigned char *>(set->h) + idx_bytes, src, src_bytes);
+    hipError_t e = hipMemcpyAsync(set->d, set->h, idx_bytes + src_bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) rc = hip_fail(e, "hipMemcpyAsync(pages)");
+    if (rc == SLORA_OK)
+        rc = launch_write_pages(pool, static_cast<const int32_t *>(set->d), n,
+                                src_on_device ? src : static_cast<const unsigned char *>(set->d) + idx_bytes, stream);
+    pool->give_set(set, stream);
     return rc;
 }
 
@@ -355,7 +549,10 @@ int32_t slora_adapter_gather(slora_pool *pool, int32_t adapter_id, int32_t slot,
     const int32_t r = it->second.rank;
     if (r > 0 && !dev_out) return fail(SLORA_EINVAL, "dev_out is NULL");
     if (r > 0 && (reinterpret_cast<uintptr_t>(dev_out) & 15)) return fail(SLORA_EINVAL, "dev_out must be 16-byte aligned");
+    DeviceScope dev(pool->device);
+    if (dev.status() != SLORA_OK) return dev.status();
     int32_t rc = pool->sync_device();
+    if (rc == SLORA_OK) rc = pool->await_arena(stream);
     if (rc != SLORA_OK) return rc;
     if (r == 0) return SLORA_OK;
     const int64_t entry = it->second.arena_off + ((int64_t)slot * 2 + which) * r;
@@ -415,7 +612,8 @@ int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *w
     const int64_t n = (int64_t)pool->n_slots * 2 * it->second.rank;
     if (n == 0) return SLORA_OK;
     if (!weights) return fail(SLORA_EINVAL, "weights is NULL");
-    HIP_TRY(hipSetDevice(pool->device));
+    DeviceScope dev(pool->device);
+    if (dev.status() != SLORA_OK) return dev.status();
     // the copy kernel dereferences `weights` on the GPU: accept only memory the runtime knows
     // (pinned host memory or device memory), never a pageable host pointer
     hipPointerAttribute_t attr;
@@ -427,6 +625,7 @@ int32_t slora_adapter_upload(slora_pool *pool, int32_t adapter_id, const void *w
     }
     if (reinterpret_cast<uintptr_t>(attr.devicePointer) & 15) return fail(SLORA_EINVAL, "weights must be 16-byte aligned");
     int32_t rc = pool->sync_device();
+    if (rc == SLORA_OK) rc = pool->await_arena(stream);
     if (rc != SLORA_OK) return rc;
     // from host memory a few workgroups saturate the link; more only queue requests in front of
     // the HBM traffic of kernels on other streams

@@ -69,6 +69,34 @@ struct Adapter {
     int64_t arena_off; // into the arena, n_slots*2*rank entries
 };
 
+// A set of buffers that one plan (or one page write) uses and then hands back to the pool: a
+// pinned host image, its device copy, and the v scratch.  Nothing is freed when a user lets
+// go: the set waits in the pool's idle list with `order` recorded on the stream that used it
+// last and is handed out again once that event has completed, so a steady stream of batches
+// (Sec. 4.1: a new batch every iteration) allocates nothing and never waits for the device.
+struct Buffers {
+    void *h = nullptr;     // pinned host memory
+    size_t h_cap = 0;
+    void *d = nullptr;     // device copy of h
+    size_t d_cap = 0;
+    float *v = nullptr;    // device scratch for v = x*A
+    size_t v_cap = 0;      // floats
+    std::vector<void *> outgrown; // device buffers replaced while work that names them may be in flight
+    void *order = nullptr; // hipEvent_t: last use of the set, or a hand-over point between streams
+};
+
+// Makes the pool's device current for the calling scope and restores the caller's device.
+class DeviceScope {
+public:
+    explicit DeviceScope(int device);
+    ~DeviceScope();
+    int32_t status() const { return rc_; }
+private:
+    int prev_ = -1;
+    bool switched_ = false;
+    int32_t rc_ = 0;
+};
+
 } // namespace slora
 
 struct slora_pool {
@@ -100,6 +128,20 @@ struct slora_pool {
     int64_t xcd_group = 0;                            // bit 0: MFMA shrink list grouped per XCD, bit 1: expand list
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
 
+    // recycled buffer sets (plans, page writes) and the stream that carries work-list uploads
+    std::vector<slora::Buffers *> idle_sets;
+    int64_t sets_made = 0;                            // buffer sets ever allocated (steady state: constant)
+    int64_t device_allocs = 0;                        // hipMalloc / hipHostMalloc calls made for them
+    void *upload_stream = nullptr;                    // hipStream_t, created on first use
+    void *arena_event = nullptr;                      // hipEvent_t: the device page-list image is complete after it
+    int32_t uploads(void **out);                      // the upload stream
+    int32_t await_arena(void *stream);                // make `stream` wait for the latest page-list upload
+
+    int32_t take_set(slora::Buffers **out, size_t h_bytes, size_t d_bytes); // an idle set whose last use has completed, or a new one
+    void give_set(slora::Buffers *set, void *last_stream);                  // record `order` on last_stream, park the set
+    int32_t grow_v(slora::Buffers *set, size_t floats);
+    void free_sets();
+
     int32_t sync_device();                            // push dirty arena range
     void set_state(int64_t page, uint8_t to);         // ownership change with free-count / stack upkeep
     int32_t take(int64_t n, uint8_t as, int32_t *out); // n free pages -> state `as`
@@ -122,23 +164,29 @@ struct slora_plan {
     std::vector<int32_t> tok_idx;                     // sorted position -> token index
     std::vector<slora::Item> vs_items, ve_items, ms_items, me_items;
 
-    // device image (one allocation)
-    void *d_blob = nullptr;
+    // device image: tok_idx and the four lists in one buffer of the plan's buffer set
+    slora::Buffers *set = nullptr;
     int32_t *d_tok_idx = nullptr;
     slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_ms = nullptr, *d_me = nullptr;
 
-    float *d_v = nullptr; // scratch for v = x*A: per slot T_act * v_stride floats (vector path rows),
-                          // then n_mfma_tiles * (v_stride/16) * pieces KiB of MFMA operand fragments
+    // scratch for v = x*A (set->v, or the library's static scratch): per slot T_act * v_stride
+    // floats (vector path rows), then n_mfma_tiles * (v_stride/16) * pieces KiB of MFMA operand
+    // fragments
     int64_t v_slot_floats(int32_t dtype) const
     {
         return (int64_t)T_act * v_stride + (int64_t)n_mfma_tiles * (v_stride / 16) * (dtype == SLORA_F16 ? 2 : 3) * 256;
     }
-    int64_t d_v_cap = 0;
-    std::vector<float *> retired_v; // outgrown scratch buffers, freed with the plan
-    int32_t v_slots = 0;  // n of the latest shrink
+    float *v_used = nullptr; // where the latest shrink left v
+    int32_t v_slots = 0;     // n of the latest shrink
+
+    // Stream order.  Every launch of a plan reads its work lists and reads or writes its v, so
+    // all of a plan's work is kept in ONE order: when a call names another stream than the
+    // previous one, the new stream first waits for an event recorded on the old one.
+    void *last_stream = nullptr; // hipStream_t of the latest upload or launch
+    bool order_recorded = false; // set->order already marks the end of the work on last_stream
 
     int32_t upload();
-    int32_t ensure_v(int32_t n);
+    int32_t enter(void *stream);
 };
 
 namespace slora {

@@ -17,6 +17,7 @@ F16, BF16 = 0, 1
 OK, EINVAL, ERANGE, EBUSY, ENOENT, ESEG, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
 MAX_MULTI = 8
 PLAN_INFO_N = 10
+POOL_STATS_N = 3
 PLAN_INFO_KEYS = ("tokens", "groups", "groups_vec", "groups_mfma", "vec_shrink_items", "vec_expand_items",
                   "mfma_shrink_items", "mfma_expand_items", "v_stride", "sum_rank")
 
@@ -49,6 +50,7 @@ def lib() -> C.CDLL:
             "slora_last_error": (C.c_char_p, []),
             "slora_pool_init": (i32, [C.POINTER(vp), i32, i64, i32, vp, i32, i32]),
             "slora_pool_destroy": (i32, [vp]),
+            "slora_pool_stats": (i32, [vp, vp, i32]),
             "slora_pool_mark_kv": (i32, [vp, vp, i64, i32]),
             "slora_pool_write_pages": (i32, [vp, vp, i64, vp, i32, vp]),
             "slora_adapter_load": (i32, [vp, i32, i32, vp, i64]),
@@ -114,6 +116,12 @@ def pool_init(page_H: int, n_pages: int, dtype: int, dev_base: Optional[int], n_
 
 def pool_destroy(pool) -> None:
     _check(lib().slora_pool_destroy(pool))
+
+
+def pool_stats(pool) -> dict:
+    out = np.zeros(POOL_STATS_N, dtype=np.int64)
+    _check(lib().slora_pool_stats(pool, _ptr(out), POOL_STATS_N))
+    return dict(zip(("sets_made", "allocations", "idle_sets"), (int(v) for v in out)))
 
 
 def pool_mark_kv(pool, page_idx, owned: bool = True) -> None:
