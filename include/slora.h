@@ -239,6 +239,26 @@ int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots
                                const void *const *x, float *const *y, void *stream);
 
 /*
+ * slora_lora_apply_multi for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same results bit for bit; the only difference is where v = x*A is kept between the two
+ * launches: in a scratch array that is part of the library's code object (one copy per GPU,
+ * SLORA_STATIC_SCRATCH_BYTES, held until the process ends) instead of the plan's own buffer.
+ * The call makes no hipMalloc / hipFree and no other allocating call, on any path.
+ * Limit: n * (tokens with an adapter * v row stride * 4 bytes + the MFMA tiles' operand
+ * fragments) must fit the scratch, else SLORA_ERANGE and nothing is enqueued (slora_plan_info
+ * gives tokens and stride; 8 slots of 4096 decode tokens at rank <= 128 need 16 MiB).
+ * Every call on a GPU uses that GPU's one array: calls whose device work may overlap (two
+ * streams, two plans, two pools) race on it - order them on one stream or by events.  Nothing
+ * in the array has to be cleared between calls: the expand reads only what the shrink of the
+ * same call wrote.  An expand on its own (slora_lora_expand) after this call reads the static
+ * scratch too, as long as no other static call came in between.
+ */
+#define SLORA_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t slora_lora_apply_multi_static(slora_plan *plan, int32_t n, const int32_t *slots,
+                                      const void *const *x, float *const *y, void *stream);
+
+/*
  * The two stages of Eq. 2 on their own (Sec. 5.3: the custom kernels compute x*A and then
  * (x*A)*B, gathering the weights from non-contiguous pool pages without padding).  shrink
  * writes v[t,:] = x[t,:] * A_i into the plan's scratch; expand adds v[t,:] * B_i onto y[t,:].

@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "slora_internal.hpp"
 
@@ -873,6 +874,17 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Scratch for callers that cannot allocate: v = x*A of one call goes here instead of into a
+// buffer from hipMalloc.  One copy per GPU, held until the process ends; every element the
+// expand reads is written by the shrink of the same call, so nothing has to start at zero.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SLORA_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices]; // device address of `scratch` on each GPU, 0 = not resolved yet
+
 int32_t check_launch(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -881,6 +893,24 @@ int32_t check_launch(const char *what)
 }
 
 } // namespace
+
+// The device address of the static scratch on `device`, which must be the current device: the
+// array's name is only a host-side handle, each GPU has its own copy at its own address.
+int32_t static_scratch_address(int device, void **out)
+{
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return fail(SLORA_EINVAL, "device %d outside [0, %d)", device, kMaxDevices);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(SLORA_EHIP, "hipGetSymbolAddress(static scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return SLORA_OK;
+}
 
 // ---------------------------------------------------------------------------------------
 // launchers

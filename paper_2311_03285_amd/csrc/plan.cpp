@@ -447,18 +447,35 @@ int32_t slora_lora_expand_y16(slora_plan *plan, int32_t n, const int32_t *slots,
 
 namespace {
 int32_t apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *const *y,
-                    void *stream, bool y16)
+                    void *stream, bool y16, bool static_scratch = false)
 {
     clear_error();
     int32_t rc = check_plan(plan, n, slots);
     if (rc != SLORA_OK) return rc;
     rc = check_y(n, y); // validate the y side before the shrink is enqueued
     if (rc != SLORA_OK) return rc;
-    rc = do_shrink(plan, n, slots, x, stream);
+    float *scratch = nullptr;
+    if (static_scratch) {
+        const int64_t need = (int64_t)n * plan->v_slot_floats(plan->pool->dtype) * (int64_t)sizeof(float);
+        if (need > (int64_t)SLORA_STATIC_SCRATCH_BYTES)
+            return fail(SLORA_ERANGE,
+                        "this batch needs %lld bytes of scratch for %d slot(s), the static scratch holds %lld: use "
+                        "fewer slots per call or slora_lora_apply_multi",
+                        (long long)need, n, (long long)SLORA_STATIC_SCRATCH_BYTES);
+        scratch = static_cast<float *>(plan->pool->static_scratch);
+        if (!scratch) return fail(SLORA_EHIP, "the static scratch was not resolved for this pool's device");
+    }
+    rc = do_shrink(plan, n, slots, x, stream, scratch);
     if (rc != SLORA_OK) return rc;
     return do_expand(plan, n, slots, y, stream, y16);
 }
 } // namespace
+
+int32_t slora_lora_apply_multi_static(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
+                                      float *const *y, void *stream)
+{
+    return apply_multi(plan, n, slots, x, reinterpret_cast<void *const *>(y), stream, false, true);
+}
 
 int32_t slora_lora_apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x,
                                float *const *y, void *stream)

@@ -352,7 +352,14 @@ int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32
     if (dev_base && (reinterpret_cast<uintptr_t>(dev_base) & 15))
         return fail(SLORA_EINVAL, "dev_base must be 16-byte aligned");
     int dev = -1;
-    if (dev_base) HIP_TRY(hipGetDevice(&dev));
+    void *static_scratch = nullptr;
+    if (dev_base) {
+        HIP_TRY(hipGetDevice(&dev));
+        // resolved here, once per GPU and with that GPU current, so that the entry point that
+        // must not allocate finds the address ready
+        int32_t rc = static_scratch_address(dev, &static_scratch);
+        if (rc != SLORA_OK) return rc;
+    }
     slora_pool *p = new (std::nothrow) slora_pool;
     if (!p) return fail(SLORA_ENOMEM, "out of host memory");
     try {
@@ -368,6 +375,7 @@ int32_t slora_pool_init(slora_pool **out, int32_t page_H, int64_t n_pages, int32
     p->n_slots = n_slots;
     p->max_rank = max_rank;
     p->device = dev;
+    p->static_scratch = static_scratch;
     p->n_free = n_pages;
     *out = p;
     return SLORA_OK;

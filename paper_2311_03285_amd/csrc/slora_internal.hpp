@@ -132,6 +132,7 @@ struct slora_pool {
     std::vector<slora::Buffers *> idle_sets;
     int64_t sets_made = 0;                            // buffer sets ever allocated (steady state: constant)
     int64_t device_allocs = 0;                        // hipMalloc / hipHostMalloc calls made for them
+    void *static_scratch = nullptr;                   // this GPU's copy of the library's static scratch
     void *upload_stream = nullptr;                    // hipStream_t, created on first use
     void *arena_event = nullptr;                      // hipEvent_t: the device page-list image is complete after it
     int32_t uploads(void **out);                      // the upload stream
@@ -199,6 +200,7 @@ int32_t build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids, int32
 int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, const void *d_src,
                            void *stream, int32_t max_groups = 0); // max_groups > 0 caps the grid
 int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void *dev_out, void *stream);
+int32_t static_scratch_address(int device, void **out); // `device` must be current
 int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
 int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16);
 

@@ -16,6 +16,7 @@ import numpy as np
 F16, BF16 = 0, 1
 OK, EINVAL, ERANGE, EBUSY, ENOENT, ESEG, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
 MAX_MULTI = 8
+STATIC_SCRATCH_BYTES = 64 << 20
 PLAN_INFO_N = 10
 POOL_STATS_N = 3
 PLAN_INFO_KEYS = ("tokens", "groups", "groups_vec", "groups_mfma", "vec_shrink_items", "vec_expand_items",
@@ -66,6 +67,7 @@ def lib() -> C.CDLL:
             "slora_lora_apply": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_apply_multi": (i32, [vp, i32, vp, vp, vp, vp]),
             "slora_lora_apply_multi_y16": (i32, [vp, i32, vp, vp, vp, vp]),
+            "slora_lora_apply_multi_static": (i32, [vp, i32, vp, vp, vp, vp]),
             "slora_lora_expand_y16": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_shrink": (i32, [vp, i32, vp, vp, vp]),
             "slora_lora_expand": (i32, [vp, i32, vp, vp, vp]),
@@ -205,6 +207,12 @@ def lora_apply(plan, slot: int, x: int, y: int, stream=None) -> None:
 def lora_apply_multi(plan, slots, xs: Sequence[int], ys: Sequence[int], stream=None) -> None:
     s = _i32(slots)
     _check(lib().slora_lora_apply_multi(plan, s.size, _ptr(s), _ptr_array(xs), _ptr_array(ys), _stream(stream)))
+
+
+def lora_apply_multi_static(plan, slots, xs: Sequence[int], ys: Sequence[int], stream=None) -> None:
+    """As lora_apply_multi, with v in the library's static scratch: allocates nothing."""
+    s = _i32(slots)
+    _check(lib().slora_lora_apply_multi_static(plan, s.size, _ptr(s), _ptr_array(xs), _ptr_array(ys), _stream(stream)))
 
 
 def lora_apply_multi_y16(plan, slots, xs: Sequence[int], ys: Sequence[int], stream=None) -> None:
