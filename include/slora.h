@@ -208,8 +208,10 @@ int32_t slora_plan_destroy(slora_plan *plan);
  *  [3] groups on the MFMA path              [4] vector shrink items   [5] vector expand items
  *  [6] MFMA shrink items                    [7] MFMA expand items     [8] v row stride (floats)
  *  [9] sum over groups of rank (pages of A read per slot)
+ *  [10] MFMA shrink tiles whose H range is shared out over several workgroups
+ *  [11] bytes of v scratch one slot of an apply needs
  */
-#define SLORA_PLAN_INFO_N 10
+#define SLORA_PLAN_INFO_N 12
 int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n);
 
 /*
@@ -303,15 +305,19 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  *   "mfma_min_tiles"   the MFMA kernels are used only if such groups make up at least this many
  *                      32-token tiles in the batch (default 32: fewer tiles cannot fill the GPU
  *                      and run faster on the vector kernels)
+ *   "mfma_split_bytes" the MFMA shrink hands the H range of a tile (up to 128 tokens x up to 128 ranks)
+ *                      to several workgroups, each taking about this many bytes of x and page rows
+ *                      (default 262144); their partial sums are added in a fixed order by a small
+ *                      second kernel
+ *   "mfma_split_min_h" ... but no share of H is shorter than this many elements (default 1024, at
+ *                      least 128), so that the partial sums stay small beside the rows
  *   "upload_groups"    workgroups of slora_adapter_upload when the source is host memory (default
  *                      32: enough requests in flight to fill the host link; many more delay the
  *                      HBM traffic of kernels running on other streams)
- *   "xcd_group"        how MFMA work items are handed to the 8 accelerator dies (one L2 each).
- *                      0 (default): round-robin.  Bit 0 (value 1): the shrink list is cut into 8
+ *   "xcd_group"        how MFMA expand items are handed to the 8 accelerator dies (one L2 each).
+ *                      0 (default): round-robin.  Bit 1 (value 2): the expand list is cut into 8
  *                      contiguous, equally heavy runs, one per die, so the tiles of an adapter
- *                      share an L2 and its pages reach the fabric once (measured: 28 % fewer
- *                      bytes fetched, duration within 2 % either way); bit 1 (value 2): the same
- *                      for the expand list (measured 13 % slower)
+ *                      share an L2 (measured 13 % slower).  Bit 0 is accepted and has no effect.
  * Results never depend on these beyond floating-point summation order.  Unknown key: EINVAL.
  */
 int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value);

@@ -486,203 +486,440 @@ __device__ __forceinline__ int64_t vfrag_index(int tile, int kk, int piece, int 
 {
     return (((int64_t)tile * n_kk + kk) * n_piece + piece) * (kWave * 8);
 }
+// eight consecutive ranks of one token -> the 16-bit pieces whose sum is the fp32 value, packed as
+// the 16 bytes a lane owns in each piece's fragment
 template <int DT>
-__device__ __forceinline__ void split_store(float f, uint16_t *frag_base, int64_t piece_stride)
+__device__ __forceinline__ void split_pieces(const float (&f)[8], u32x4 (&piece)[VPieces<DT>::N])
 {
-    if constexpr (DT == SLORA_F16) {
-        const _Float16 a = (_Float16)f;
-        const _Float16 b = (_Float16)(f - (float)a);
-        frag_base[0] = __builtin_bit_cast(uint16_t, a);
-        frag_base[piece_stride] = __builtin_bit_cast(uint16_t, b);
-    } else {
-        const uint32_t h = __float_as_uint(f) & 0xffff0000u;
-        const float r1 = f - __uint_as_float(h);
-        const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
-        const float r2 = r1 - __uint_as_float(m);
-        frag_base[0] = (uint16_t)(h >> 16);
-        frag_base[piece_stride] = (uint16_t)(m >> 16);
-        frag_base[2 * piece_stride] = (uint16_t)(__float_as_uint(r2) >> 16);
+    uint16_t h[VPieces<DT>::N][8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if constexpr (DT == SLORA_F16) {
+            const _Float16 a = (_Float16)f[e];
+            const _Float16 b = (_Float16)(f[e] - (float)a);
+            h[0][e] = __builtin_bit_cast(uint16_t, a);
+            h[1][e] = __builtin_bit_cast(uint16_t, b);
+        } else {
+            const uint32_t hi = __float_as_uint(f[e]) & 0xffff0000u;
+            const float r1 = f[e] - __uint_as_float(hi);
+            const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+            const float r2 = r1 - __uint_as_float(mid);
+            h[0][e] = (uint16_t)(hi >> 16);
+            h[1][e] = (uint16_t)(mid >> 16);
+            h[2][e] = (uint16_t)(__float_as_uint(r2) >> 16);
+        }
     }
+#pragma unroll
+    for (int p = 0; p < VPieces<DT>::N; ++p)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) piece[p][k] = (uint32_t)h[p][2 * k] | ((uint32_t)h[p][2 * k + 1] << 16);
 }
 
 // ---------------------------------------------------------------------------------------
-// prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for up to 64 tokens of one adapter
-// (MB = 1 or 2 MFMA blocks of 32 rows) and up to 64 of its ranks (NB = 1 or 2 blocks).
+// prefill shrink: V[pos, j] = sum_h x[tok, h] * Apage_j[h] for up to 128 tokens of one adapter
+// (MB = 2 or 4 blocks of 32 rows, one per wavefront), up to 128 of its ranks (NB = 1, 2 or 4
+// blocks of 32) and a range of H.
 //
-// A classic LDS-tiled product with the second operand gathered through the page list.  H is
-// walked in chunks of 128 elements.  Per chunk the workgroup copies the x rows and the page
-// rows (256 bytes of each) into LDS with fully coalesced 16-byte loads - 16 adjacent lanes
-// read one row's 256 bytes, so a wavefront instruction touches 8 cache lines instead of the 32
-// a load in MFMA operand layout would - through a register ring that keeps three chunks in
-// flight per workgroup.  LDS rows are padded by 16 bytes; the four wavefronts take two of the
-// chunk's eight 16-element k-steps each, read their operands in MFMA layout with 16-byte LDS
-// loads and accumulate full partial tiles, which are summed through LDS in a fixed order at
-// the end and written once (no atomics) as operand fragments of the expand.  Token rows beyond
-// the item and ranks beyond the adapter's are read from a valid row instead; their results are
-// not stored, or stored as zero (ranks up to the next multiple of 32, so the expand can read
-// whole blocks).  Two token blocks per item halve the number of times the pages are read.
+// An LDS-tiled product with the second operand gathered through the page list.  The range of H
+// is walked in chunks of 64 elements.  Per chunk the workgroup copies the x rows and the page
+// rows (128 bytes of each) into LDS; the rows are fetched 256 bytes at a time with coalesced
+// 16-byte loads through a register ring that keeps two such granules in flight.  LDS rows are
+// padded by 16 bytes; wavefront w owns token block w, reads its operands in MFMA layout with
+// 16-byte LDS loads and accumulates 32 x 32 tiles for all rank blocks, so no sum across
+// wavefronts is needed.  Large tiles (128 tokens share every page row) keep the pages from
+// being fetched once per 32 or 64 tokens.
+//
+// A workgroup streams its rows at a rate set by the loads it keeps in flight, so the scheduler
+// cuts the H range of a tile into n_parts shares, one workgroup each.  A share leaves its
+// partial sums (fp32) in the slot's scratch; a second, small kernel (join_shares_kernel, one
+// workgroup per split tile) adds them up in the order of their numbers.  The kernel boundary
+// is the only synchronisation: arrival counters with device-wide fences inside the shrink were
+// tried and cost more than the extra launch (a fence per workgroup writes back and invalidates
+// the die's whole L2: cfg3's shrink went from 77 us unsplit to 93 us with 168 shares).
+//
+// The finished tile goes to the expand as MFMA operand fragments (see VPieces).  For binary16
+// pools every token row is first scaled by a power of two, 2^e, that puts its largest |v| into
+// [2^10, 2^11): the hi piece then holds 11 bits and the lo piece 11 more whatever the magnitude
+// of v, and v up to 2^35 cannot overflow the 16-bit format.  e (clamped to [-24, 40]) is left
+// beside the fragments; the expand scales its accumulators by 2^e and back.
+// Token rows beyond the item and ranks beyond the adapter's are read from a valid row instead;
+// their results are not stored, or stored as zero (ranks up to the next multiple of 32, so the
+// expand can read whole blocks).
 // ---------------------------------------------------------------------------------------
 constexpr int kMfmaThreads = 256;
-constexpr int kMfmaBlocks = kMfmaRanks / 32;     // 32-rank MFMA blocks per shrink item
-constexpr int kChunkH = 128;                     // elements of H per chunk
-constexpr int kChunkBytes = kChunkH * 2;         // bytes of one row per chunk
-constexpr int kLdsRow = kChunkBytes + 16;        // padded LDS row
-constexpr int kTileRows = 32 * kMfmaShrinkTiles + kMfmaRanks; // x rows, then page rows
-constexpr int kRing = 3;                         // chunks in flight
-constexpr int kRowsPerPass = kMfmaThreads / 16;  // rows covered by one load per thread
+constexpr int kMsChunk = kMsGranule / 2;             // elements of H per LDS chunk
+constexpr int kMsRowBytes = kMsChunk * 2;            // bytes of one row per chunk
+constexpr int kMsGranuleBytes = kMsGranule * 2;      // bytes of one row fetched at a time
+constexpr int kMsLdsRow = kMsRowBytes + 16;          // padded LDS row
+constexpr int kRing = 2;                             // granules in flight
+constexpr int kMsRowsPerPass = kMfmaThreads / 8;     // rows covered by one load per thread
+constexpr int kEpiStride = 36;                       // floats per row of a wavefront's 32 x 32 staging tile
+constexpr int kExpMin = -24, kExpMax = 40;           // range of the row exponents of binary16 pools
+static_assert(kMsRowsPerPass == 32 && kMsTok == 128 && kMsRanks == 128, "copy duty and tile shape are tied");
+
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((uint32_t)(e + 127) << 23); }
+
+// Partial sums of a split tile: [share][token block][rank block][octet pair i][lane][8 floats];
+// lane l holds token l % 32 of its wavefront's block and the rank octets l / 32 + 2 i.
+template <int NB>
+__device__ __forceinline__ void store_share(const MsItem &it, int wave, int lane, const float (&val)[NB][2][8],
+                                            float *__restrict__ partial)
+{
+    const int mb_act = (it.ntok + 31) >> 5, nb_act = (it.nj + 31) >> 5;
+    const int64_t blk = (int64_t)mb_act * nb_act * 1024;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        if (nb < nb_act) {
+            float *dst = partial + it.part * blk + (int64_t)(wave * nb_act + nb) * 1024 + lane * 8;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                *reinterpret_cast<f32x4 *>(dst + i * 512) = f32x4{val[nb][i][0], val[nb][i][1], val[nb][i][2], val[nb][i][3]};
+                *reinterpret_cast<f32x4 *>(dst + i * 512 + 4) =
+                    f32x4{val[nb][i][4], val[nb][i][5], val[nb][i][6], val[nb][i][7]};
+            }
+        }
+    }
+}
+
+// Exponent e of the power of two that scales a token row of a binary16 pool: the row's largest
+// |v| lands in [2^10, 2^11).  Zero, subnormal, infinite and NaN maxima get e = 0.
+__device__ __forceinline__ int row_exponent(float vmax)
+{
+    const int be = (int)((__float_as_uint(vmax) >> 23) & 0xffu); // biased exponent of the row maximum
+    if (be == 0 || be == 255) return 0;
+    return min(max(10 - (be - 127), kExpMin), kExpMax);
+}
+
+// Ranks beyond the adapter's become zero; returns the largest |value| this lane holds in the block.
+__device__ __forceinline__ float mask_block(const MsItem &it, int nb, int q, float (&val)[2][8])
+{
+    float vmax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int jn = nb * 32 + (q + 2 * i) * 8 + e;
+            const float f = jn < it.nj ? val[i][e] : 0.f;
+            val[i][e] = f;
+            vmax = fmaxf(vmax, fabsf(f));
+        }
+    return vmax;
+}
+
+// One 32-token x 32-rank block of finished sums -> the two operand fragments it fills (lane l:
+// token l % 32, rank octets l / 32 and l / 32 + 2), scaled by `sc` first.
+template <int DT>
+__device__ __forceinline__ void store_block(const MsItem &it, int tile, int nb, int lane, const float (&val)[2][8],
+                                            float sc, int v_stride, uint16_t *__restrict__ vfrag)
+{
+    constexpr int NP = VPieces<DT>::N;
+    const int n_kk = v_stride >> 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int kk = (it.j0 >> 4) + 2 * nb + i;
+        if (kk < n_kk) {
+            float f[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) f[k] = DT == SLORA_F16 ? val[i][k] * sc : val[i][k];
+            uint16_t *dst = vfrag + vfrag_index(tile, kk, 0, n_kk, NP) + lane * 8;
+            u32x4 piece[NP];
+            split_pieces<DT>(f, piece);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) *reinterpret_cast<u32x4 *>(dst + p * (kWave * 8)) = piece[p];
+        }
+    }
+}
+
+// Row exponents are kept as signed bytes, 32 per (v tile, rank block), ordered so that the 16
+// exponents a lane of the expand needs - accumulator register 4 g + k of lane half q holds row
+// 8 g + 4 q + k - are the 16 consecutive bytes q * 16 + g * 4 + k: one 16-byte load.
+__device__ __forceinline__ int8_t *vexp_row(int8_t *vexp, const MsItem &it, int tile, int v_stride, int row)
+{
+    const int n_rb = (v_stride + kMsRanks - 1) / kMsRanks;
+    const int g = row >> 3, qq = (row >> 2) & 1, k = row & 3;
+    return vexp + ((int64_t)tile * n_rb + it.j0 / kMsRanks) * 32 + qq * 16 + g * 4 + k;
+}
+
+// The finished sums of one token block (this wavefront's), all rank blocks -> operand fragments.
+template <int DT, int NB>
+__device__ __forceinline__ void finish_tile(const MsItem &it, int wave, int lane, float (&val)[NB][2][8], int v_stride,
+                                            uint16_t *__restrict__ vfrag, int8_t *__restrict__ vexp)
+{
+    const int row = lane & 31, q = lane >> 5;
+    const int nb_act = (it.nj + 31) >> 5;
+    const bool token_ok = wave * 32 + row < it.ntok;
+    float vmax = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+        if (nb < nb_act) vmax = fmaxf(vmax, mask_block(it, nb, q, val[nb]));
+    float sc = 1.f;
+    if constexpr (DT == SLORA_F16) {
+        vmax = fmaxf(vmax, __shfl_xor(vmax, 32, kWave)); // the other half of the token's ranks
+        const int e = row_exponent(vmax);
+        sc = pow2f(e);
+        if (q == 0) *vexp_row(vexp, it, it.tile + wave, v_stride, row) = (int8_t)(token_ok ? e : 0);
+    }
+    if (!token_ok) return;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+        if (nb < nb_act) store_block<DT>(it, it.tile + wave, nb, lane, val[nb], sc, v_stride, vfrag);
+}
 
 template <int DT, int NB, int MB>
-__device__ __forceinline__ void shrink_mfma_tile(const Item &it, const int32_t *__restrict__ pa,
+__device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t *__restrict__ pa,
                                                  const unsigned char *__restrict__ x,
                                                  const uint16_t *__restrict__ pool,
                                                  const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                 uint16_t *__restrict__ vfrag, unsigned char *lds)
+                                                 uint16_t *__restrict__ vfrag, int8_t *__restrict__ vexp,
+                                                 float *__restrict__ partial, unsigned char *lds)
 {
-    constexpr int kLoadsX = MB * 32 / kRowsPerPass; // x rows copied per thread (2 or 4)
-    constexpr int kLoadsP = NB * 32 / kRowsPerPass; // page rows copied per thread (2 or 4)
-    constexpr int kLoads = kLoadsX + kLoadsP;
+    constexpr int kLoads = MB + NB;                 // 16-byte loads per thread and chunk
     constexpr int kRows = 32 * (MB + NB);           // LDS rows of one buffer
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int row = lane & 31;
     const int q = lane >> 5;
-    const int j0 = it.a, nj = it.b;
     const int64_t row_bytes = (int64_t)H * 2;
 
-    // ---- copy duty of this thread: byte column cb of LDS rows r16 + 16*i (x rows, then pages)
-    const int r16 = tid >> 4;
-    const int cb = (tid & 15) * 16;
+    // ---- copy duty of this thread: byte column cb of LDS rows r8 + 32*i (x rows, then pages)
+    const int r8 = tid >> 3;
+    const int cb = (tid & 7) * 16;
     const unsigned char *src[kLoads];
 #pragma unroll
-    for (int i = 0; i < kLoadsX; ++i) {
-        const int r = r16 + kRowsPerPass * i;
+    for (int i = 0; i < MB; ++i) {
+        const int r = r8 + kMsRowsPerPass * i;
         src[i] = x + (int64_t)tok_idx[it.pos0 + (r < it.ntok ? r : 0)] * row_bytes;
     }
 #pragma unroll
-    for (int i = 0; i < kLoadsP; ++i) {
-        const int j = r16 + kRowsPerPass * i;
-        src[kLoadsX + i] = reinterpret_cast<const unsigned char *>(pool) + (int64_t)pa[j < nj ? j : 0] * row_bytes;
+    for (int i = 0; i < NB; ++i) {
+        const int j = r8 + kMsRowsPerPass * i;
+        src[MB + i] = reinterpret_cast<const unsigned char *>(pool) + (int64_t)pa[j < it.nj ? j : 0] * row_bytes;
     }
-    const int n_chunks = (H + kChunkH - 1) / kChunkH;
+    const int n_gran = it.c1 - it.c0;
 
+    // Memory is read in granules of 256 bytes per row (two LDS chunks): a thread fetches the two
+    // 16-byte pieces cb and cb + 128 of a granule back to back, so the two 128-byte lines of a
+    // granule are requested together (128-byte pieces fetched a chunk apart ran at two thirds of
+    // the rate).
     struct Regs {
-        u32x4 w[kLoads];
+        u32x4 w[2][kLoads];
     };
-    auto load = [&](int c, Regs &r) { // chunk c (clamped to the last one), bytes clamped into the row
-        const int cc = min(c, n_chunks - 1);
-        const int64_t off = min((int64_t)cc * kChunkBytes + cb, row_bytes - 16);
+    auto load = [&](int g, Regs &r) { // granule g of the share (clamped to its last one), bytes clamped into the row
+        const int gg = it.c0 + min(g, n_gran - 1);
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i) r.w[i] = *reinterpret_cast<const u32x4 *>(src[i] + off);
+        for (int h = 0; h < 2; ++h) {
+            const int64_t off = min((int64_t)gg * kMsGranuleBytes + h * kMsRowBytes + cb, row_bytes - 16);
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+                // x rows are read once: streaming loads; page rows come back for the adapter's other
+                // token tiles and stay cacheable (measured on 8192-token batches of rank 8 / 128:
+                // all plain 77 / 115 us, all streaming 68 / 121 us)
+                if (i < MB)
+                    r.w[h][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src[i] + off));
+                else
+                    r.w[h][i] = *reinterpret_cast<const u32x4 *>(src[i] + off);
+            }
+        }
     };
-    auto stash = [&](int c, const Regs &r) { // registers -> LDS buffer c & 1; bytes past the row become zero
-        unsigned char *buf = lds + (c & 1) * (kRows * kLdsRow);
-        const bool ok = (int64_t)c * kChunkBytes + cb < row_bytes;
+    auto stash = [&](int g, int h, const Regs &r) { // half h of granule g -> LDS buffer h; bytes past the row become zero
+        unsigned char *buf = lds + h * (kRows * kMsLdsRow);
+        const bool ok = (int64_t)(it.c0 + g) * kMsGranuleBytes + h * kMsRowBytes + cb < row_bytes;
         const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
-            *reinterpret_cast<u32x4 *>(buf + (r16 + kRowsPerPass * i) * kLdsRow + cb) = ok ? r.w[i] : zero;
+            *reinterpret_cast<u32x4 *>(buf + (r8 + kMsRowsPerPass * i) * kMsLdsRow + cb) = ok ? r.w[h][i] : zero;
     };
-    f32x16 acc[MB][NB];
+    f32x16 acc[NB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+    auto compute = [&](int h) { // the four k-steps of the chunk in LDS buffer h, for this wavefront's token block
+        if (wave >= MB) return;
+        const unsigned char *buf = lds + h * (kRows * kMsLdsRow);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
-    auto compute = [&](int c) { // this wavefront's two k-steps of chunk c
-        const unsigned char *buf = lds + (c & 1) * (kRows * kLdsRow);
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const int kb = (2 * wave + k) * 32 + q * 16; // byte offset of this lane's 8 k-values in the row
-            u32x4 xa[MB], pb[NB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                xa[mb] = *reinterpret_cast<const u32x4 *>(buf + (mb * 32 + row) * kLdsRow + kb);
+        for (int k = 0; k < kMsChunk / 16; ++k) {
+            const int kb = k * 32 + q * 16; // byte offset of this lane's 8 k-values in the row
+            const u32x4 xa = *reinterpret_cast<const u32x4 *>(buf + (wave * 32 + row) * kMsLdsRow + kb);
+            u32x4 pb[NB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                pb[nb] = *reinterpret_cast<const u32x4 *>(buf + (32 * MB + nb * 32 + row) * kLdsRow + kb);
+                pb[nb] = *reinterpret_cast<const u32x4 *>(buf + (32 * MB + nb * 32 + row) * kMsLdsRow + kb);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma32<DT>(xa[mb], pb[nb], acc[mb][nb]);
+            for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32<DT>(xa, pb[nb], acc[nb]);
         }
     };
 
-    // register ring: chunk c is copied to LDS while chunks c+1 .. c+kRing-1 are still in flight
-    // and chunk c+kRing is requested (chunks past the end re-read the last one and are dropped)
+    // register ring: granule g is copied to LDS, half by half, while granule g+1 is still in
+    // flight and granule g+kRing is requested (granules past the end re-read the last one and
+    // are dropped).  The two halves use the two LDS buffers, one barrier each.
     Regs ring[kRing];
 #pragma unroll
     for (int d = 0; d < kRing; ++d) {
         load(d, ring[d]);
-        // keep the three chunks' loads in issue order: the wait before a chunk is copied to LDS
-        // then counts only the loads of the two younger chunks as outstanding
+        // keep the granules' loads in issue order: the wait before a granule is copied to LDS
+        // then counts only the loads of the younger one as outstanding
         __builtin_amdgcn_sched_barrier(0);
     }
-    const int n_rounds = (n_chunks + kRing - 1) / kRing;
+    const int n_rounds = (n_gran + kRing - 1) / kRing;
     for (int rd = 0; rd < n_rounds; ++rd) {
 #pragma unroll
         for (int d = 0; d < kRing; ++d) {
-            const int c = rd * kRing + d;
-            stash(c, ring[d]);
-            load(c + kRing, ring[d]);
+            const int g = rd * kRing + d;
+            stash(g, 0, ring[d]);
             __syncthreads();
-            if (c < n_chunks) compute(c);
+            if (g < n_gran) compute(0);
+            stash(g, 1, ring[d]);
+            load(g + kRing, ring[d]);
+            __syncthreads();
+            if (g < n_gran) compute(1);
         }
     }
-    __syncthreads();
+    __syncthreads(); // the chunk buffers are free: each wavefront now stages its tiles in its own part
 
-    float(*red)[16][kWave] = reinterpret_cast<float(*)[16][kWave]>(lds);
-    constexpr int NP = VPieces<DT>::N;
+    // ---- accumulator layout -> 8 consecutive ranks of one token per lane -------------------
+    // lane l ends up with token l % 32 of its wavefront's v tile and, per 32-rank block, the rank
+    // octets l / 32 and l / 32 + 2: exactly the 16 bytes it owns in two operand fragments.
+    const int mb_act = (it.ntok + 31) >> 5;          // token blocks / rank blocks that exist
+    const int nb_act = (it.nj + 31) >> 5;
+    const bool live = wave < mb_act;
+    float *stage = reinterpret_cast<float *>(lds) + wave * 32 * kEpiStride;
+    float val[NB][2][8];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+    for (int nb = 0; nb < NB; ++nb) {
+        if (live && nb < nb_act) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
+            for (int vv = 0; vv < 16; ++vv) stage[mfma_row(vv, lane) * kEpiStride + row] = acc[nb][vv];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-            for (int e = 0; e < 16; ++e) red[wave][e][lane] = acc[mb][nb][e];
-            __syncthreads();
-            for (int e = tid; e < 16 * kWave; e += kMfmaThreads) {
-                const int vv = e >> 6, l = e & 63;
-                const float s = (red[0][vv][l] + red[1][vv][l]) + (red[2][vv][l] + red[3][vv][l]);
-                const int i = mfma_row(vv, l);   // token row inside v tile it.tile + mb
-                const int jn = nb * 32 + (l & 31);
-                const int j = j0 + jn;           // rank; ranks past the adapter's own are stored as zero
-                uint16_t *dst = vfrag + vfrag_index(it.tile + mb, j >> 4, 0, v_stride >> 4, NP) +
-                                (i + 32 * ((j & 15) >> 3)) * 8 + (j & 7);
-                if (mb * 32 + i < it.ntok) split_store<DT>(jn < nj ? s : 0.f, dst, kWave * 8);
+            for (int i = 0; i < 2; ++i) {
+                const int oct = q + 2 * i;
+                const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * kEpiStride + oct * 8);
+                const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * kEpiStride + oct * 8 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    val[nb][i][e] = lo[e];
+                    val[nb][i][4 + e] = hi[e];
+                }
             }
-            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
+
+    // ---- a share of a split tile: leave the partial sums for join_shares_kernel ----------------
+    if (it.n_parts > 1) {
+        if (live) store_share<NB>(it, wave, lane, val, partial);
+        return;
+    }
+    if (live) finish_tile<DT, NB>(it, wave, lane, val, v_stride, vfrag, vexp);
 }
 
 template <int DT>
-__global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const Item *__restrict__ items,
+__global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const MsItem *__restrict__ items,
                                                                        const int32_t *__restrict__ arena,
                                                                        const uint16_t *__restrict__ pool,
                                                                        const int32_t *__restrict__ tok_idx, int H,
                                                                        int v_stride, MultiArgs args)
 {
-    static_assert(kMfmaBlocks == 2 && kMfmaShrinkTiles == 2, "tile shapes of the scheduler and the kernel differ");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kTileRows * kLdsRow];
-    static_assert(sizeof(lds) >= 4 * 16 * kWave * sizeof(float), "reduction buffer must fit");
-    const int cs = mfma_slot_of(blockIdx.x, args.n);
-    const Item it = items[mfma_item_of(blockIdx.x, args.n)];
-    if (it.ntok == 0) return; // padding of a short per-XCD list
+    // two chunk buffers of (128 token rows + the plan's widest rank block) padded rows, sized at
+    // launch: a batch of low-rank adapters leaves room for more workgroups per compute unit
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    // slots vary fastest: the shares of a tile, and the tiles of an adapter, follow one another
+    const int cs = blockIdx.x % args.n;
+    const MsItem it = items[blockIdx.x / args.n];
     const unsigned char *x = static_cast<const unsigned char *>(args.x[cs]);
-    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a;
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.j0;
     uint16_t *vfrag = reinterpret_cast<uint16_t *>(args.v[cs] + args.vfrag_off);
-    if (it.ntok <= 32) {
-        if (it.b <= 32)
-            shrink_mfma_tile<DT, 1, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
-        else
-            shrink_mfma_tile<DT, 2, 1>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+    int8_t *vexp = reinterpret_cast<int8_t *>(args.v[cs] + args.vexp_off);
+    float *partial = args.v[cs] + args.part_off + it.part_off;
+#define SLORA_MS(NBV, MBV) shrink_mfma_tile<DT, NBV, MBV>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, vexp, partial, lds)
+    if (it.ntok <= 64) {
+        if (it.nj <= 32) SLORA_MS(1, 2);
+        else if (it.nj <= 64) SLORA_MS(2, 2);
+        else SLORA_MS(4, 2);
     } else {
-        if (it.b <= 32)
-            shrink_mfma_tile<DT, 1, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
-        else
-            shrink_mfma_tile<DT, 2, 2>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, lds);
+        if (it.nj <= 32) SLORA_MS(1, 4);
+        else if (it.nj <= 64) SLORA_MS(2, 4);
+        else SLORA_MS(4, 4);
     }
+#undef SLORA_MS
+}
+
+// One workgroup per split tile, token block and slot; its wavefront nb adds up the shares of rank
+// block nb in the order of their numbers (a fixed order: the same bits on every run; the loads of
+// four shares are in flight at a time) and finishes the block as the shrink itself does for a
+// tile that was not split.  Binary16: the row maximum over the rank blocks meets in LDS.
+template <int DT>
+__global__ __launch_bounds__(kMfmaThreads) void join_shares_kernel(const MsItem *__restrict__ tiles, int v_stride,
+                                                                    MultiArgs args)
+{
+    constexpr int kBlocks = kMsTok / 32;
+    __shared__ float smax[kMsRanks / 32][32];
+    const int cs = blockIdx.x % args.n;
+    const int tb = (blockIdx.x / args.n) % kBlocks;          // token block
+    const MsItem it = tiles[blockIdx.x / args.n / kBlocks];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int nb = threadIdx.x / kWave;                       // rank block of this wavefront
+    const int row = lane & 31, q = lane >> 5;
+    const int mb_act = (it.ntok + 31) >> 5, nb_act = (it.nj + 31) >> 5;
+    if (tb >= mb_act) return;                                 // the whole workgroup
+    const bool live = nb < nb_act;
+    float val[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[i][e] = 0.f;
+    if (live) {
+        const int64_t blk = (int64_t)mb_act * nb_act * 1024;
+        const float *base = args.v[cs] + args.part_off + it.part_off + (int64_t)(tb * nb_act + nb) * 1024 + lane * 8;
+        constexpr int kBatch = 4;
+        for (int p0 = 0; p0 < it.n_parts; p0 += kBatch) {
+            f32x4 w[kBatch][4];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const float *srcp = base + (int64_t)min(p0 + k, it.n_parts - 1) * blk;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    w[k][2 * i] = *reinterpret_cast<const f32x4 *>(srcp + i * 512);
+                    w[k][2 * i + 1] = *reinterpret_cast<const f32x4 *>(srcp + i * 512 + 4);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                if (p0 + k < it.n_parts) {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            val[i][e] += w[k][2 * i][e];
+                            val[i][4 + e] += w[k][2 * i + 1][e];
+                        }
+                }
+            }
+        }
+    }
+    float sc = 1.f;
+    const bool token_ok = tb * 32 + row < it.ntok;
+    float vmax = live ? mask_block(it, nb, q, val) : 0.f;
+    if constexpr (DT == SLORA_F16) {
+        vmax = fmaxf(vmax, __shfl_xor(vmax, 32, kWave));
+        if (q == 0) smax[nb][row] = vmax;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kMsRanks / 32; ++k) vmax = fmaxf(vmax, smax[k][row]);
+        const int e = row_exponent(vmax);
+        sc = pow2f(e);
+        if (nb == 0 && q == 0)
+            *vexp_row(reinterpret_cast<int8_t *>(args.v[cs] + args.vexp_off), it, it.tile + tb, v_stride, row) = (int8_t)(token_ok ? e : 0);
+    }
+    if (live && token_ok)
+        store_block<DT>(it, it.tile + tb, nb, lane, val, sc, v_stride,
+                        reinterpret_cast<uint16_t *>(args.v[cs] + args.vfrag_off));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -765,6 +1002,16 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
         }
     };
     load_pg(0);
+    // row exponents of the tile's first rank block (binary16 pools), see below
+    typedef int32_t e_i32x4 __attribute__((ext_vector_type(4)));
+    [[maybe_unused]] const e_i32x4 *vexp_t = nullptr;
+    [[maybe_unused]] e_i32x4 e_cur = e_i32x4{0, 0, 0, 0};
+    if constexpr (DT == SLORA_F16) {
+        const int n_rb = (v_stride + kMsRanks - 1) / kMsRanks;
+        vexp_t = reinterpret_cast<const e_i32x4 *>(reinterpret_cast<const int8_t *>(args.v[cs] + args.vexp_off) +
+                                                   (int64_t)it.tile * n_rb * 32 + q * 16);
+        e_cur = vexp_t[0];
+    }
 
     // accumulators start as the y tile (rows / columns outside the tile read a valid element)
     f32x16 acc[2];
@@ -804,8 +1051,34 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // the stages overwrite the slab
     }
+    // binary16 pools: the shrink scaled token row i of rank block rb (kMsRanks ranks) by 2^e[rb][i].
+    // The accumulators follow: they hold (y + products so far) * 2^e of the CURRENT rank block -
+    // scaled up before the first block, re-scaled where the block changes, scaled back at the end.
+    // Powers of two: every step is exact.  A lane's 16 exponents of a block are one 16-byte load,
+    // requested with the first page numbers (e_cur) so that it has arrived when y has.
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    [[maybe_unused]] auto scale_rows = [&](const i32x4 &from, const i32x4 &to) { // acc *= 2^(to - from), row by row
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int d = (int)(int8_t)(to[g] >> (8 * k)) - (int)(int8_t)(from[g] >> (8 * k));
+                const float f = pow2f(d);
+                acc[0][4 * g + k] *= f;
+                acc[1][4 * g + k] *= f;
+            }
+    };
+    [[maybe_unused]] const i32x4 e_zero = i32x4{0, 0, 0, 0};
+    if constexpr (DT == SLORA_F16) scale_rows(e_zero, e_cur);
 
     for (int k0 = 0; k0 < it.rank; k0 += 32) {
+        if constexpr (DT == SLORA_F16) {
+            if (k0 > 0 && (k0 & (kMsRanks - 1)) == 0) {
+                const i32x4 e_next = vexp_t[(k0 / kMsRanks) * 2];
+                scale_rows(e_cur, e_next);
+                e_cur = e_next;
+            }
+        }
         // ---- operands of this stage: two B rows per lane and round, V for both k-steps
         u32x4 wa[2], wb[2];
 #pragma unroll
@@ -848,6 +1121,7 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
         }
     }
 
+    if constexpr (DT == SLORA_F16) scale_rows(e_cur, e_zero);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int vv = 0; vv < 16; ++vv)
@@ -970,14 +1244,29 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     }
     if (!plan->ms_items.empty()) {
         const dim3 grid((unsigned)(plan->ms_items.size() * (size_t)n));
+        // LDS: the kernel's two chunk buffers for the widest tile of this plan (never less than the
+        // four staging tiles of the epilogue)
+        const int nb_max = plan->ms_max_nj <= 32 ? 1 : plan->ms_max_nj <= 64 ? 2 : 4;
+        const size_t lds = std::max<size_t>((size_t)2 * (kMsTok + 32 * nb_max) * kMsLdsRow, (size_t)4 * 32 * kEpiStride * sizeof(float));
         if (pool->dtype == SLORA_F16)
-            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
+            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_F16>, grid, dim3(kMfmaThreads), lds, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         else
-            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_BF16>, grid, dim3(kMfmaThreads), 0, st, plan->d_ms,
+            hipLaunchKernelGGL(shrink_mfma_kernel<SLORA_BF16>, grid, dim3(kMfmaThreads), lds, st, plan->d_ms,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);
         int32_t rc = check_launch("shrink_mfma");
         if (rc != SLORA_OK) return rc;
+        if (plan->n_sync > 0) {
+            const dim3 jgrid((unsigned)((size_t)plan->n_sync * (kMsTok / 32) * (size_t)n));
+            if (pool->dtype == SLORA_F16)
+                hipLaunchKernelGGL(join_shares_kernel<SLORA_F16>, jgrid, dim3(kMfmaThreads), 0, st, plan->d_mj,
+                                   plan->v_stride, args);
+            else
+                hipLaunchKernelGGL(join_shares_kernel<SLORA_BF16>, jgrid, dim3(kMfmaThreads), 0, st, plan->d_mj,
+                                   plan->v_stride, args);
+            rc = check_launch("join_shares");
+            if (rc != SLORA_OK) return rc;
+        }
     }
     return SLORA_OK;
 }

@@ -120,12 +120,17 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         plan->vs_items.clear();
         plan->ve_items.clear();
         plan->ms_items.clear();
+        plan->mj_items.clear();
         plan->me_items.clear();
         plan->sum_rank = 0;
         plan->n_groups = (int32_t)order.size();
         plan->n_groups_vec = plan->n_groups_mfma = 0;
         plan->n_mfma_tiles = 0;
+        plan->n_sync = 0;
+        plan->ms_max_nj = 0;
+        plan->part_floats = 0;
         plan->max_shrink_tok = 0;
+        const int32_t n_chunks = (pool->H + kMsGranule - 1) / kMsGranule;
         int32_t max_rank = 0;
         const int32_t H = pool->H;
         // The MFMA kernels pay off when adapters have many tokens AND there are enough 32-token
@@ -137,6 +142,20 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
             if (n >= pool->mfma_min_tokens) mfma_tiles += (n + kMfmaTok - 1) / kMfmaTok;
         }
         const int64_t min_tokens = mfma_tiles >= pool->mfma_min_tiles ? pool->mfma_min_tokens : INT64_MAX;
+        // Size of a share of an MFMA shrink tile (see below): mfma_split_bytes, or more when the
+        // batch is so large that shares of that size would be far more than the GPU can hold at a
+        // time (every share of a split tile costs a set of partial sums) - about three workgroups
+        // per compute unit for a launch of up to eight slots.
+        int64_t ms_bytes = 0;
+        for (int32_t gi : order) {
+            const Group &g = groups[(size_t)gi];
+            const int64_t n = (int64_t)g.toks.size();
+            if (n < min_tokens) continue;
+            const int64_t n_tok_tiles = (n + kMsTok - 1) / kMsTok, n_rank_blocks = (g.rank + kMsRanks - 1) / kMsRanks;
+            ms_bytes += (n * n_rank_blocks + (int64_t)g.rank * n_tok_tiles) * H * 2;
+        }
+        const int64_t launch_slots = std::min<int64_t>(pool->n_slots, SLORA_MAX_MULTI);
+        const int64_t share_bytes = std::max<int64_t>(pool->mfma_split_bytes, ms_bytes * launch_slots / (3 * 256));
         int32_t n_vec_groups = 0;
         for (int32_t gi : order)
             if ((int64_t)groups[(size_t)gi].toks.size() < min_tokens) n_vec_groups++;
@@ -162,16 +181,51 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
             if ((int64_t)n >= min_tokens) {
                 plan->n_groups_mfma++;
                 // v tiles of 32 tokens, numbered in order; an expand item covers one tile, a shrink
-                // item kMfmaShrinkTiles consecutive ones (its pages are then read once for them all)
+                // item up to four consecutive ones (its pages are then read once for them all)
                 const int32_t tile0 = plan->n_mfma_tiles;
                 const int32_t n_tiles = (n + kMfmaTok - 1) / kMfmaTok;
                 plan->n_mfma_tiles += n_tiles;
-                for (int32_t t = 0; t < n_tiles; t += kMfmaShrinkTiles) {
-                    const int32_t p = t * kMfmaTok;
-                    const int32_t nt = std::min(kMfmaShrinkTiles * kMfmaTok, n - p);
-                    for (int32_t j = 0; j < g.rank; j += kMfmaRanks)
-                        plan->ms_items.push_back(
-                            Item{off, g.rank, j, std::min(kMfmaRanks, g.rank - j), pos_base + p, nt, tile0 + t, 0});
+                for (int32_t p = 0; p < n; p += kMsTok) {
+                    const int32_t nt = std::min(kMsTok, n - p);
+                    for (int32_t j = 0; j < g.rank; j += kMsRanks) {
+                        const int32_t nj = std::min(kMsRanks, g.rank - j);
+                        // Shares of H: a workgroup streams its rows at a rate set by what it keeps in
+                        // flight, so a tile of (nt + nj) rows x H is cut into shares of about
+                        // share_bytes each - the launch then consists of many workgroups of
+                        // similar, small size and every compute unit is busy to the end.  A share is
+                        // never shorter than mfma_split_min_h elements: the partial sums a share
+                        // leaves behind (and the last one reads back) must stay small beside its rows.
+                        const int64_t cost = (int64_t)(nt + nj) * H * 2;
+                        int64_t parts = (cost + share_bytes / 2) / share_bytes;
+                        parts = std::min<int64_t>(parts, H / std::max<int64_t>(pool->mfma_split_min_h, kMsGranule));
+                        parts = std::min<int64_t>(parts, std::min<int64_t>(n_chunks, 64));
+                        const int64_t mb = (nt + 31) / 32, nb = (nj + 31) / 32;
+                        if (parts < 2 || plan->part_floats + parts * mb * nb * 1024 > (int64_t(1) << 30))
+                            parts = 1;
+                        plan->ms_max_nj = std::max(plan->ms_max_nj, nj);
+                        MsItem it{};
+                        it.arena_off = off;
+                        it.rank = g.rank;
+                        it.j0 = j;
+                        it.nj = nj;
+                        it.pos0 = pos_base + p;
+                        it.ntok = nt;
+                        it.tile = tile0 + p / kMfmaTok;
+                        it.n_parts = (int32_t)parts;
+                        it.sync = -1;
+                        if (parts > 1) {
+                            it.sync = plan->n_sync++;
+                            it.part_off = (int32_t)plan->part_floats;
+                            plan->part_floats += parts * mb * nb * 1024;
+                            plan->mj_items.push_back(it);
+                        }
+                        for (int32_t q = 0; q < (int32_t)parts; ++q) {
+                            it.part = q;
+                            it.c0 = (int32_t)((int64_t)n_chunks * q / parts);
+                            it.c1 = (int32_t)((int64_t)n_chunks * (q + 1) / parts);
+                            plan->ms_items.push_back(it);
+                        }
+                    }
                 }
                 for (int32_t t = 0; t < n_tiles; ++t) {
                     const int32_t p = t * kMfmaTok;
@@ -196,10 +250,16 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
             }
         }
-        xcd_layout(plan->ms_items, [H](const Item &i) { return (int64_t)(i.ntok + i.b) * H * 2; }, (pool->xcd_group & 1) != 0);
+        // longest first: the hardware hands a workgroup to a compute unit as one becomes free, so
+        // with the big shares at the head of the list and the small ones at its end the launch
+        // ends on every unit at about the same time
+        std::stable_sort(plan->ms_items.begin(), plan->ms_items.end(), [](const MsItem &a, const MsItem &b) {
+            return (int64_t)(a.ntok + a.nj) * (a.c1 - a.c0) > (int64_t)(b.ntok + b.nj) * (b.c1 - b.c0);
+        });
         xcd_layout(plan->me_items, [](const Item &i) { return (int64_t)i.b * (i.ntok * 8 + i.rank * 2); }, (pool->xcd_group & 2) != 0);
         plan->T_act = (int32_t)plan->tok_idx.size();
         plan->v_stride = std::max(kRankPad, (max_rank + kRankPad - 1) / kRankPad * kRankPad);
+        plan->n_rank_blocks = (plan->v_stride + kMsRanks - 1) / kMsRanks;
     } catch (const std::bad_alloc &) {
         return fail(SLORA_ENOMEM, "out of host memory while planning");
     }
@@ -210,10 +270,10 @@ int32_t slora_plan::upload()
 {
     if (!pool->dev_base) return SLORA_OK; // host-only pool: the plan stays on the host
     const size_t n_tok = tok_idx.size();
-    const size_t n_items = vs_items.size() + ve_items.size() + ms_items.size() + me_items.size();
     if (n_tok == 0) return SLORA_OK;
-    const size_t tok_bytes = (n_tok * sizeof(int32_t) + 31) / 32 * 32;
-    const size_t bytes = tok_bytes + n_items * sizeof(Item);
+    const size_t tok_bytes = (n_tok * sizeof(int32_t) + 63) / 64 * 64;
+    const size_t bytes = tok_bytes + (ms_items.size() + mj_items.size()) * sizeof(MsItem) +
+                         (vs_items.size() + ve_items.size() + me_items.size()) * sizeof(Item);
     // The image is assembled in the pinned half of a recycled buffer set and copied to the
     // device half on the pool's own upload stream: the copy runs beside whatever the caller's
     // streams are doing, and the first launch of the plan waits for it through an event.
@@ -222,13 +282,15 @@ int32_t slora_plan::upload()
     unsigned char *img = static_cast<unsigned char *>(set->h);
     std::memcpy(img, tok_idx.data(), n_tok * sizeof(int32_t));
     unsigned char *at = img + tok_bytes;
-    auto put = [&](const std::vector<Item> &v) {
-        if (!v.empty()) std::memcpy(at, v.data(), v.size() * sizeof(Item));
-        at += v.size() * sizeof(Item);
+    auto put = [&](const auto &v) {
+        const size_t n_bytes = v.size() * sizeof(v[0]);
+        if (!v.empty()) std::memcpy(at, v.data(), n_bytes);
+        at += n_bytes;
     };
+    put(ms_items); // 64-byte records first: everything stays aligned to its size
+    put(mj_items);
     put(vs_items);
     put(ve_items);
-    put(ms_items);
     put(me_items);
     void *up_v = nullptr;
     rc = pool->uploads(&up_v);
@@ -249,11 +311,21 @@ int32_t slora_plan::upload()
     last_stream = pool->upload_stream;
     order_recorded = true;
     d_tok_idx = (int32_t *)set->d;
-    d_vs = (Item *)((unsigned char *)set->d + tok_bytes);
+    d_ms = (MsItem *)((unsigned char *)set->d + tok_bytes);
+    d_mj = d_ms + ms_items.size();
+    d_vs = (Item *)(d_mj + mj_items.size());
     d_ve = d_vs + vs_items.size();
-    d_ms = d_ve + ve_items.size();
-    d_me = d_ms + ms_items.size();
+    d_me = d_ve + ve_items.size();
     return SLORA_OK;
+}
+
+void slora_plan::fill_args(MultiArgs &a, int32_t n, float *v) const
+{
+    const int64_t per_slot = v_slot_floats(pool->dtype);
+    for (int32_t k = 0; k < n; ++k) a.v[k] = v + (int64_t)k * per_slot;
+    a.vfrag_off = (int64_t)T_act * v_stride;
+    a.vexp_off = a.vfrag_off + vfrag_floats(pool->dtype);
+    a.part_off = a.vexp_off + vexp_floats();
 }
 
 int32_t slora_plan::enter(void *stream)
@@ -301,17 +373,15 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
     DeviceScope dev(plan->pool->device);
     if (dev.status() != SLORA_OK) return dev.status();
     // the page lists of every adapter the plan names went to the device when it was built
-    const int64_t need = (int64_t)n * plan->v_slot_floats(plan->pool->dtype);
     float *v = scratch;
     int32_t rc = SLORA_OK;
     if (!v) {
-        rc = plan->pool->grow_v(plan->set, (size_t)need);
+        rc = plan->pool->grow_v(plan->set, (size_t)plan->v_total_floats(n, plan->pool->dtype));
         v = plan->set->v;
     }
     if (rc == SLORA_OK) rc = plan->enter(stream);
     if (rc != SLORA_OK) return rc;
-    for (int32_t k = 0; k < n; ++k) a.v[k] = v + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
-    a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
+    plan->fill_args(a, n, v);
     rc = launch_shrink(plan, n, a, stream);
     if (rc == SLORA_OK) {
         plan->v_slots = n;
@@ -349,8 +419,7 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const
     if (dev.status() != SLORA_OK) return dev.status();
     rc = plan->enter(stream);
     if (rc != SLORA_OK) return rc;
-    for (int32_t k = 0; k < n; ++k) a.v[k] = plan->v_used + (int64_t)k * plan->v_slot_floats(plan->pool->dtype);
-    a.vfrag_off = (int64_t)plan->T_act * plan->v_stride;
+    plan->fill_args(a, n, plan->v_used);
     return launch_expand(plan, n, a, stream, y16);
 }
 
@@ -416,10 +485,12 @@ int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n)
                                           plan->n_groups_mfma,
                                           (int64_t)plan->vs_items.size(),
                                           (int64_t)plan->ve_items.size(),
-                                          live(plan->ms_items),
+                                          (int64_t)plan->ms_items.size(),
                                           live(plan->me_items),
                                           plan->v_stride,
-                                          plan->sum_rank};
+                                          plan->sum_rank,
+                                          plan->n_sync,
+                                          plan->v_slot_floats(plan->pool->dtype) * (int64_t)sizeof(float)};
     for (int32_t k = 0; k < n; ++k) out[k] = v[k];
     return SLORA_OK;
 }
@@ -456,7 +527,7 @@ int32_t apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const voi
     if (rc != SLORA_OK) return rc;
     float *scratch = nullptr;
     if (static_scratch) {
-        const int64_t need = (int64_t)n * plan->v_slot_floats(plan->pool->dtype) * (int64_t)sizeof(float);
+        const int64_t need = plan->v_total_floats(n, plan->pool->dtype) * (int64_t)sizeof(float);
         if (need > (int64_t)SLORA_STATIC_SCRATCH_BYTES)
             return fail(SLORA_ERANGE,
                         "this batch needs %lld bytes of scratch for %d slot(s), the static scratch holds %lld: use "

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstdarg>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -82,7 +83,7 @@ int32_t slora_pool::take_set(Buffers **out, size_t h_bytes, size_t d_bytes)
         }
         if (q != hipSuccess) return hip_fail(q, "hipEventQuery");
         set = c;
-        idle_sets.erase(idle_sets.begin() + (ptrdiff_t)k);
+        idle_sets.erase(idle_sets.begin() + (std::ptrdiff_t)k);
         break;
     }
     if (!set) {
@@ -653,6 +654,16 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
     if (!std::strcmp(key, "mfma_min_tiles")) {
         if (value < 1) return fail(SLORA_EINVAL, "mfma_min_tiles must be >= 1");
         pool->mfma_min_tiles = value;
+        return SLORA_OK;
+    }
+    if (!std::strcmp(key, "mfma_split_bytes")) {
+        if (value < 4096) return fail(SLORA_EINVAL, "mfma_split_bytes must be >= 4096");
+        pool->mfma_split_bytes = value;
+        return SLORA_OK;
+    }
+    if (!std::strcmp(key, "mfma_split_min_h")) {
+        if (value < 128) return fail(SLORA_EINVAL, "mfma_split_min_h must be >= 128");
+        pool->mfma_split_min_h = value;
         return SLORA_OK;
     }
     if (!std::strcmp(key, "upload_groups")) {

@@ -23,8 +23,8 @@ const char *last_error_cstr();
 // One record type serves the four work lists; `a` and `b` mean
 //   vector shrink : a = first page j0 of the A list, b = number of pages
 //   vector expand : a = first column (element index),  b = number of columns
-//   MFMA   shrink : a = first rank j0 (multiple of kMfmaRanks), b = number of ranks (<= kMfmaRanks)
 //   MFMA   expand : a = first column (element index),  b = number of columns
+// (the MFMA shrink has its own record, MsItem)
 struct Item {
     int32_t arena_off; // adapter's first entry in the page-list arena ([slot][A r][B r])
     int32_t rank;      // r of the adapter
@@ -37,6 +37,24 @@ struct Item {
 };
 static_assert(sizeof(Item) == 32, "Item must stay 32 bytes");
 
+// MFMA shrink item: up to kMsTok tokens of one adapter x up to kMsRanks of its ranks x a range
+// of H.  The range is the whole of H, or one of n_parts shares of it: then the workgroups of a
+// tile leave their partial sums in the slot's scratch and a second kernel adds them up in the
+// order of the shares.
+struct MsItem {
+    int32_t arena_off; // adapter's first entry in the page-list arena
+    int32_t rank;      // r of the adapter
+    int32_t j0, nj;    // first rank (a multiple of kMsRanks) and number of ranks
+    int32_t pos0, ntok; // first position in the sorted token list, tokens
+    int32_t tile;      // v tile (32 tokens) of the first token; the item covers up to 4 consecutive tiles
+    int32_t c0, c1;    // granules [c0, c1) of H, kMsGranule elements each
+    int32_t part, n_parts;
+    int32_t sync;      // number of the tile among the plan's split tiles (-1: not split)
+    int32_t part_off;  // floats from the slot's partial area to the tile's partial sums
+    int32_t pad[3];
+};
+static_assert(sizeof(MsItem) == 64, "MsItem must stay 64 bytes");
+
 // Per-launch arguments for up to SLORA_MAX_MULTI slots handled by one grid.
 struct MultiArgs {
     const void *x[SLORA_MAX_MULTI];
@@ -45,6 +63,8 @@ struct MultiArgs {
     int32_t slot[SLORA_MAX_MULTI];
     int32_t n; // slots in this launch; workgroup b handles item b / n for slot entry b % n
     int64_t vfrag_off; // floats from v[k] to the slot's v tiles in MFMA operand layout
+    int64_t vexp_off;  // floats from v[k] to the per-row exponents of the tiles (binary16 pools)
+    int64_t part_off;  // floats from v[k] to the partial sums of split tiles
 };
 
 // Tile constants the scheduler and the kernels must agree on.
@@ -53,8 +73,9 @@ constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandColsMax = 1024; // most columns per vector-expand item (a multiple of 512, <= 4096; measured best on cfg4: 1024)
 constexpr int kMfmaTok = 32;      // tokens per v tile = per MFMA-expand item (one 32-row MFMA block)
-constexpr int kMfmaShrinkTiles = 2; // v tiles (32 tokens each) per MFMA-shrink item
-constexpr int kMfmaRanks = 64;    // ranks per MFMA-shrink item (two 32-column MFMA blocks)
+constexpr int kMsTok = 128;       // tokens per MFMA-shrink item (one 32-row block per wavefront)
+constexpr int kMsRanks = 128;     // ranks per MFMA-shrink item (up to four 32-column blocks per wavefront)
+constexpr int kMsGranule = 128;   // elements of H the MFMA shrink fetches per row at a time; shares of H are whole granules
 constexpr int kMfmaExpandCols = 256; // columns per MFMA-expand item (4 wavefronts x 64)
 constexpr int kXcds = 8;         // accelerator dies (each with its own L2); MFMA lists are padded to this
 constexpr int kRankPad = 32;      // v rows are zero-padded to a multiple of this many ranks
@@ -127,6 +148,8 @@ struct slora_pool {
     int64_t mfma_min_tiles = 32;
     int64_t xcd_group = 0;                            // bit 0: MFMA shrink list grouped per XCD, bit 1: expand list
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
+    int64_t mfma_split_bytes = 256 << 10;             // MFMA shrink: a tile's H range is cut into shares of about this many row bytes
+    int64_t mfma_split_min_h = 1024;                  // ... but no share is shorter than this many elements of H
 
     // recycled buffer sets (plans, page writes) and the stream that carries work-list uploads
     std::vector<slora::Buffers *> idle_sets;
@@ -163,20 +186,33 @@ struct slora_plan {
 
     // host image
     std::vector<int32_t> tok_idx;                     // sorted position -> token index
-    std::vector<slora::Item> vs_items, ve_items, ms_items, me_items;
+    std::vector<slora::Item> vs_items, ve_items, me_items;
+    std::vector<slora::MsItem> ms_items;
+    std::vector<slora::MsItem> mj_items; // one record per split tile, for the kernel that joins the shares
+    int32_t ms_max_nj = 0;     // most ranks in one MFMA shrink item (sizes the kernel's LDS)
+    int32_t n_sync = 0;        // split tiles
+    int64_t part_floats = 0;   // partial sums of the split tiles, per slot
+    int32_t n_rank_blocks = 1; // kMsRanks-blocks per row of v (exponent sets per tile)
 
     // device image: tok_idx and the four lists in one buffer of the plan's buffer set
     slora::Buffers *set = nullptr;
     int32_t *d_tok_idx = nullptr;
-    slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_ms = nullptr, *d_me = nullptr;
+    slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_me = nullptr;
+    slora::MsItem *d_ms = nullptr, *d_mj = nullptr;
 
-    // scratch for v = x*A (set->v, or the library's static scratch): per slot T_act * v_stride
-    // floats (vector path rows), then n_mfma_tiles * (v_stride/16) * pieces KiB of MFMA operand
-    // fragments
+    // scratch for v = x*A (set->v, or the library's static scratch), per slot: T_act * v_stride floats (vector path rows), n_mfma_tiles * (v_stride/16) *
+    // pieces KiB of MFMA operand fragments, 32 row exponents (bytes) per tile and rank block, and the
+    // partial sums of split tiles
+    int64_t vfrag_floats(int32_t dtype) const
+    {
+        return (int64_t)n_mfma_tiles * (v_stride / 16) * (dtype == SLORA_F16 ? 2 : 3) * 256;
+    }
+    int64_t vexp_floats() const { return (int64_t)n_mfma_tiles * n_rank_blocks * 8; } // one byte per row
     int64_t v_slot_floats(int32_t dtype) const
     {
-        return (int64_t)T_act * v_stride + (int64_t)n_mfma_tiles * (v_stride / 16) * (dtype == SLORA_F16 ? 2 : 3) * 256;
+        return (int64_t)T_act * v_stride + vfrag_floats(dtype) + vexp_floats() + part_floats;
     }
+    int64_t v_total_floats(int32_t n, int32_t dtype) const { return (int64_t)n * v_slot_floats(dtype); }
     float *v_used = nullptr; // where the latest shrink left v
     int32_t v_slots = 0;     // n of the latest shrink
 
@@ -188,6 +224,7 @@ struct slora_plan {
 
     int32_t upload();
     int32_t enter(void *stream);
+    void fill_args(slora::MultiArgs &a, int32_t n, float *v) const;
 };
 
 namespace slora {

@@ -197,3 +197,156 @@ def test_eight_slots_in_one_launch_pair():
         with pytest.raises(slora.SloraError):  # nine slots are refused before anything is launched
             slora.lora_apply_multi(plan, slots + [0], [t.data_ptr() for t in xs + xs[:1]],
                                    [t.data_ptr() for t in ys + ys[:1]])
+
+
+# ------------------------------------------------------------------ H shared out over workgroups
+def split(pool, nbytes=4096, min_h=128):
+    """Force the MFMA shrink to cut every tile's H range into many small shares."""
+    slora.set_option(pool, "mfma_split_bytes", nbytes)
+    slora.set_option(pool, "mfma_split_min_h", min_h)
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("H", [320, 1000, 4096])
+def test_shares_of_H_add_up_to_the_oracle(dtype, H):
+    w = prefill_workload(500 + H, dtype, H=H)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, MFMA_ALL)
+        whole = gpu_slot(dw, 0, dw.plan())
+        split(dw.pool)
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        assert info["split_tiles"] > 0 and info["mfma_shrink_items"] >= 2 * info["split_tiles"]
+        for slot in range(w.n_slots):
+            got = gpu_slot(dw, slot, plan)
+            rel, _ = assert_close(got, oracle_slot(w, slot), f"split H={H} slot={slot}")
+            assert rel <= 5e-6, rel
+        rel, _ = errors(gpu_slot(dw, 0, plan), whole.astype(np.float64))
+        assert rel <= 2e-6                      # the two summation orders agree to rounding
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_shares_of_H_integer_inputs_bit_exact_and_deterministic(dtype):
+    w = prefill_workload(520, dtype, H=1000, int_valued=True)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, MFMA_ALL)
+        split(dw.pool)
+        plan = dw.plan()
+        assert np.array_equal(gpu_slot(dw, 1, plan).astype(np.float64), oracle_slot(w, 1))
+    w = prefill_workload(521, dtype, H=4096, n_slots=4, n_pages=4000)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, MFMA_ALL)
+        split(dw.pool, 16384, 128)
+        plan = dw.plan()
+        # whichever share arrives last adds the shares in the same order: the same bits every time,
+        # in one launch for four slots as in four launches
+        first = [gpu_slot(dw, s, plan) for s in range(4)]
+        for rep in range(4):
+            xs = [dw.x_dev(s) for s in range(4)]
+            ys = [dw.y_dev(s) for s in range(4)]
+            slora.lora_apply_multi(plan, [0, 1, 2, 3], [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+            torch.cuda.synchronize()
+            for s in range(4):
+                assert np.array_equal(ys[s].cpu().numpy(), first[s]), (rep, s)
+
+
+@pytest.mark.parametrize("log2_scale", [-12, -6, 6, 12])
+def test_fp16_v_far_from_unit_scale(log2_scale):
+    """The 16-bit pieces that carry v into the MFMA expand must hold fp32 precision whatever the
+    magnitude of v (activations far from N(0,1)): against the oracle on the delta alone, and
+    against the vector kernels on the same batch."""
+    w = prefill_workload(530, synth.F16, H=1000, y_zero=True)
+    from paper_2311_03285_amd.synth import round_to_bits
+    g = np.random.default_rng(530 + log2_scale)
+    xb = round_to_bits(g.standard_normal((w.T, w.H)).astype(np.float32) * np.float32(2.0 ** log2_scale), w.dtype)
+    ref = oracle_slot(w, 0, x_bits=xb)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        outs = {}
+        for name, thr in (("mfma", MFMA_ALL), ("vec", VEC_ONLY)):
+            route(dw.pool, thr)
+            outs[name] = gpu_slot(dw, 0, dw.plan(), x_bits=xb)
+            assert np.isfinite(outs[name]).all()
+            rel, _ = errors(outs[name], ref)
+            assert rel <= 5e-6, (name, log2_scale, rel)
+        split(dw.pool)
+        route(dw.pool, MFMA_ALL)
+        rel, _ = errors(gpu_slot(dw, 0, dw.plan(), x_bits=xb), ref)
+        assert rel <= 5e-6, ("mfma, shared out", log2_scale, rel)
+
+
+# ------------------------------------------------------------------ invariances on the MFMA path
+@pytest.mark.parametrize("shares", [False, True])
+def test_mfma_page_placement_invariance(shares):
+    """Same weights at other page indices: no reduction order depends on page numbers, so the
+    MFMA path too gives bit-identical results."""
+    w1 = prefill_workload(540, synth.F16, H=512)
+    w2 = prefill_workload(540, synth.F16, H=512, n_pages=3700)
+    w2.page_idx = [(p.astype(np.int64) * 2 + 1).astype(np.int32) for p in w1.page_idx]
+    outs = []
+    for w in (w1, w2):
+        with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+            route(dw.pool, MFMA_ALL)
+            if shares:
+                split(dw.pool)
+            outs.append(gpu_slot(dw, 1))
+    assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_mfma_request_permutation(dtype):
+    """Requests in another order (tokens of a request stay together): every output row is the
+    same up to the rounding of a different tile alignment, and right against the oracle."""
+    w = prefill_workload(550, dtype, H=512)
+    n_seg = w.seg_offsets.size - 1
+    order = np.random.default_rng(2).permutation(n_seg)
+    rows = np.concatenate([np.arange(w.seg_offsets[s], w.seg_offsets[s + 1]) for s in order])
+    seg2 = np.concatenate([[0], np.cumsum(np.diff(w.seg_offsets)[order])]).astype(np.int32)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, MFMA_ALL)
+        a = gpu_slot(dw, 0)
+        p2 = dw.plan(ids=w.ids[rows], seg_offsets=seg2)
+        b = gpu_slot(dw, 0, p2, x_bits=w.x_bits(0)[rows], y_in=w.y_in(0)[rows])
+        assert_close(b, oracle_slot(w, 0)[rows], "permuted requests")
+        rel, _ = errors(b, a[rows].astype(np.float64))
+        assert rel <= 1e-6
+        # token order scrambled inside the batch as well (a pure-decode description of the same ids)
+        perm = np.random.default_rng(3).permutation(w.T)
+        p3 = dw.plan(ids=w.ids[perm], seg_offsets=None)
+        c = gpu_slot(dw, 0, p3, x_bits=w.x_bits(0)[perm], y_in=w.y_in(0)[perm])
+        assert_close(c, oracle_slot(w, 0)[perm], "permuted tokens")
+        rel, _ = errors(c, a[perm].astype(np.float64))
+        assert rel <= 1e-6
+
+
+# ------------------------------------------------------------------ every slot of the timed shapes
+def _all_slots(n):
+    """Every slot of a full-size configuration, eight slots per launch pair as the bench times
+    it, against the oracle on a seeded sample of tokens (the oracle computes them one by one)."""
+    w = synth.config(n)
+    slots = list(range(w.n_slots))
+    act = np.nonzero(w.ids >= 0)[0]
+    samp = np.sort(np.random.default_rng(n).choice(act, size=min(act.size, 96), replace=False))
+    ids_s = np.full_like(w.ids, -1)
+    ids_s[samp] = w.ids[samp]
+    with DeviceWorkload(w, real_adapters=np.unique(w.ids[samp]), slots=slots) as dw:
+        plan = dw.plan()
+        for g0 in range(0, len(slots), slora.MAX_MULTI):
+            grp = slots[g0:g0 + slora.MAX_MULTI]
+            xs = [dw.x_dev(s) for s in grp]
+            ys = [dw.y_dev(s) for s in grp]
+            slora.lora_apply_multi(plan, grp, [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+            torch.cuda.synchronize()
+            for s, t in zip(grp, ys):
+                got = t.cpu().numpy()[samp]
+                assert np.isfinite(got).all(), s
+                ref = oracle_slot(w, s, ids=ids_s)[samp]
+                rel, _ = assert_close(got, ref, f"cfg{n} slot {s}")
+                assert rel <= 5e-6, (s, rel)
+
+
+def test_config3_every_slot():
+    _all_slots(3)
+
+
+def test_config5_every_slot():
+    _all_slots(5)
