@@ -1,0 +1,69 @@
+"""The padded batched-matmul formulation the paper compares its kernels with (Sec. 7.1, the
+"bmm" variant: every token's adapter gathered into contiguous tensors padded to the batch's
+largest rank, then two batched matrix products) beside the paged kernels, on a ragged batch.
+
+(i)  the library's output against the fp64 oracle at the spec bars;
+(ii) the padded-bmm output against the same oracle.  That formulation keeps v = x A and the
+     delta in the 16-bit storage type, so its bar is the 16-bit rounding, not fp32: relative L2
+     error of the delta <= 2e-3 (binary16: two roundings of relative size 2^-11) or <= 1.6e-2
+     (bfloat16: 2^-8).
+The gathers are done by the library (slora_adapter_gather); the matrix products by the GPU's
+library GEMM through torch.bmm - a baseline to measure against, never a part of the path."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2311_03285_amd import slora, synth
+from paper_2311_03285_amd.harness import DeviceWorkload, bits_to_device
+from gpu_util import assert_close, errors, oracle_slot
+from test_gpu_mfma import prefill_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def padded_bmm(dw, w, slot, x16, y32):
+    """y32[t] += (x[t] A_pad[t]) B_pad[t] with A_pad / B_pad gathered per TOKEN and zero-padded."""
+    tdt = torch.float16 if w.dtype == synth.F16 else torch.bfloat16
+    act = np.nonzero((w.ids >= 0) & (w.ranks[np.maximum(w.ids, 0)] > 0))[0]
+    rmax = int(w.ranks[w.ids[act]].max())
+    A = torch.zeros((act.size, rmax, w.H), dtype=torch.int16, device=dw.device)
+    B = torch.zeros_like(A)
+    for k, t in enumerate(act):
+        a = int(w.ids[t])
+        r = int(w.ranks[a])
+        slora.adapter_gather(dw.pool, a, slot, 0, A[k].data_ptr())      # r rows of H: the columns of A
+        slora.adapter_gather(dw.pool, a, slot, 1, B[k].data_ptr())      # the rows of B
+        assert r <= rmax
+    act_d = torch.from_numpy(act).to(dw.device)
+    xv = x16.view(tdt)[act_d].unsqueeze(1)                               # [T, 1, H]
+    v = torch.bmm(xv, A.view(tdt).transpose(1, 2))                       # [T, 1, rmax], 16-bit
+    y32[act_d] += torch.bmm(v, B.view(tdt)).squeeze(1).float()           # delta in 16 bits, added in fp32
+    return rmax
+
+
+@pytest.mark.parametrize("dtype,bar", [(synth.F16, 2e-3), (synth.BF16, 1.6e-2)])
+def test_padded_bmm_formulation_beside_the_paged_kernels(dtype, bar):
+    w = prefill_workload(700 + dtype, dtype, H=512, y_zero=True, lens=(1, 2, 31, 40, 1, 64, 1, 100, 7, 1))
+    ref = oracle_slot(w, 1)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        slora.set_option(dw.pool, "mfma_min_tiles", 1)                  # a small batch: still use both kernel families
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        assert info["groups_vec"] > 0 and info["groups_mfma"] > 0       # decode-like and prefill-like groups
+        x = bits_to_device(w.x_bits(1), dw.device)
+        y = torch.zeros((w.T, w.H), dtype=torch.float32, device=dw.device)
+        slora.lora_apply(plan, 1, x.data_ptr(), y.data_ptr())
+        torch.cuda.synchronize()
+        ours = y.cpu().numpy()
+        rel, _ = assert_close(ours, ref, "paged kernels")               # (i) spec bars
+        assert rel <= 5e-6
+        yb = torch.zeros_like(y)
+        rmax = padded_bmm(dw, w, 1, x, yb)
+        torch.cuda.synchronize()
+        bmm = yb.cpu().numpy()
+        assert rmax == 160
+        rel_b, _ = errors(bmm, ref)                                      # (ii) 16-bit bar
+        assert np.isfinite(bmm).all() and rel_b <= bar, rel_b
+        assert rel_b > 20 * rel                                          # and that is what fp32 v buys
+        untouched = (w.ids < 0) | (w.ranks[np.maximum(w.ids, 0)] == 0)
+        assert not bmm[untouched].any() and not ours[untouched].any()
