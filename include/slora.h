@@ -210,8 +210,9 @@ int32_t slora_plan_destroy(slora_plan *plan);
  *  [9] sum over groups of rank (pages of A read per slot)
  *  [10] MFMA shrink tiles whose H range is shared out over several workgroups
  *  [11] bytes of v scratch one slot of an apply needs
+ *  [12] adapter groups an apply serves with the one-launch decode kernel
  */
-#define SLORA_PLAN_INFO_N 12
+#define SLORA_PLAN_INFO_N 13
 int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n);
 
 /*
@@ -311,6 +312,12 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  *                      second kernel
  *   "mfma_split_min_h" ... but no share of H is shorter than this many elements (default 1024, at
  *                      least 128), so that the partial sums stay small beside the rows
+ *   "fuse_decode"      adapter groups of at most 4 tokens (decode) can run both stages in ONE launch, a
+ *                      workgroup per group: 1 (default) when the batch has enough such groups to
+ *                      fill the GPU and they average 1 MiB of pages or more, 0 never, 2 always.  Applies only (the two-stage calls
+ *                      slora_lora_shrink / slora_lora_expand always use the two kernels, and an
+ *                      expand on its own needs a slora_lora_shrink before it, not an apply).
+ *   "shrink_pages"     pages of A per work item of the decode shrink (default 4)
  *   "upload_groups"    workgroups of slora_adapter_upload when the source is host memory (default
  *                      32: enough requests in flight to fill the host link; many more delay the
  *                      HBM traffic of kernels running on other streams)

@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void gather_pages_kernel(const uint16_t *__res
 // ---------------------------------------------------------------------------------------
 // decode path, shrink: v[pos, j] = sum_h x[tok, h] * Apage_j[h]
 //
-// One workgroup (4 wavefronts) = one item = up to kShrinkPages pages of one adapter and up to
+// One workgroup (4 wavefronts) = one item = a few pages of one adapter (shrink_pages) and up to
 // kShrinkTok tokens that use it.  The tokens' x rows are staged once in LDS.  Each wavefront
 // streams whole pages from HBM (pages wave, wave+4, ... of the item) with 16-byte non-temporal
 // loads per lane, U loads per block, two blocks in flight (the next block - possibly of the
@@ -180,32 +180,24 @@ __global__ __launch_bounds__(256) void gather_pages_kernel(const uint16_t *__res
 constexpr int kShrinkThreads = 256;
 constexpr int kShrinkWaves = kShrinkThreads / kWave;
 
-template <int DT, int U>
-__global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *__restrict__ items,
-                                                                     const int32_t *__restrict__ arena,
-                                                                     const uint16_t *__restrict__ pool,
-                                                                     const int32_t *__restrict__ tok_idx, int H,
-                                                                     int v_stride, MultiArgs args)
+// The wavefront's share of `n_pages` consecutive entries of a page list (entries wave, wave + nw,
+// ...), dotted against the `ntok` x rows staged in LDS; put(t, j, s) receives the finished sum
+// of token t and list entry j (lane 0 only).  stage() copies the x rows to LDS and ends with a
+// workgroup barrier; it runs after the first block of page data has been requested.
+template <int DT, int U, class Stage, class Put>
+__device__ __forceinline__ void shrink_vec_core(const int32_t *__restrict__ pa, int n_pages, int ntok, int wave, int nw,
+                                                int lane, const uint16_t *__restrict__ pool, int H,
+                                                const u32x4 *xs, Stage stage, Put put)
 {
-    extern __shared__ u32x4 xs[]; // [ntok][H/8]
-    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
-    const int cs = blockIdx.x % args.n;
-    const Item it = items[blockIdx.x / args.n];
-    const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
-    float *__restrict__ v = args.v[cs];
     const int nch = H >> 3; // 16-byte chunks per row
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
     const int nblk = (nch + kWave * U - 1) / (kWave * U);                           // blocks per page
-    const int my_pages = it.b > wave ? (it.b - wave + kShrinkWaves - 1) / kShrinkWaves : 0;
+    const int my_pages = n_pages > wave ? (n_pages - wave + nw - 1) / nw : 0;
     const int total = my_pages * nblk;
-    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a + wave;
     const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 
     // block `blk` of this wavefront's page number `pg`
     auto load_block = [&](int pg, int blk, u32x4(&w)[U]) {
-        const u32x4 *page = reinterpret_cast<const u32x4 *>(pool + (int64_t)pa[pg * kShrinkWaves] * H);
+        const u32x4 *page = reinterpret_cast<const u32x4 *>(pool + (int64_t)pa[wave + pg * nw] * H);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = (blk * U + u) * kWave + lane;
@@ -218,7 +210,7 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
     auto consume = [&](int pg, int blk, const u32x4(&w)[U]) {
 #pragma unroll
         for (int t = 0; t < kShrinkTok; ++t) {
-            if (t < it.ntok) {
+            if (t < ntok) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int c = (blk * U + u) * kWave + lane;
@@ -228,12 +220,12 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
             }
         }
         if (blk == nblk - 1) {
-            const int j = it.a + wave + pg * kShrinkWaves;
+            const int j = wave + pg * nw;
 #pragma unroll
             for (int t = 0; t < kShrinkTok; ++t) {
-                if (t < it.ntok) {
+                if (t < ntok) {
                     const float s = wave_sum(acc[t]);
-                    if (lane == 0) v[(int64_t)(it.pos0 + t) * v_stride + j] = s;
+                    if (lane == 0) put(t, j, s);
                 }
                 acc[t] = 0.f;
             }
@@ -242,12 +234,7 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
 
     u32x4 wa[U], wb[U];
     if (total > 0) load_block(0, 0, wa);
-
-    for (int t = 0; t < it.ntok; ++t) {
-        const u32x4 *row = reinterpret_cast<const u32x4 *>(x + (int64_t)tok_idx[it.pos0 + t] * H);
-        for (int c = tid; c < nch; c += kShrinkThreads) xs[t * nch + c] = row[c];
-    }
-    __syncthreads();
+    stage();
 
     int pg = 0, blk = 0;       // position of the block held in wa
     for (int b = 0; b < total; b += 2) {
@@ -262,6 +249,34 @@ __global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *
         pg = pg2;
         blk = blk2;
     }
+}
+
+template <int DT, int U>
+__global__ __launch_bounds__(kShrinkThreads) void shrink_vec_kernel(const Item *__restrict__ items,
+                                                                     const int32_t *__restrict__ arena,
+                                                                     const uint16_t *__restrict__ pool,
+                                                                     const int32_t *__restrict__ tok_idx, int H,
+                                                                     int v_stride, MultiArgs args)
+{
+    extern __shared__ u32x4 xs[]; // [ntok][H/8]
+    // slots vary fastest, so workgroups are dispatched in the order of the work list (by rank)
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
+    const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
+    float *__restrict__ v = args.v[cs];
+    const int nch = H >> 3;
+    const int tid = threadIdx.x;
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank + it.a;
+    shrink_vec_core<DT, U>(
+        pa, it.b, it.ntok, tid / kWave, kShrinkWaves, tid & (kWave - 1), pool, H, xs,
+        [&]() {
+            for (int t = 0; t < it.ntok; ++t) {
+                const u32x4 *row = reinterpret_cast<const u32x4 *>(x + (int64_t)tok_idx[it.pos0 + t] * H);
+                for (int c = tid; c < nch; c += kShrinkThreads) xs[t * nch + c] = row[c];
+            }
+            __syncthreads();
+        },
+        [&](int t, int j, float s) { v[(int64_t)(it.pos0 + t) * v_stride + it.a + j] = s; });
 }
 
 // ---------------------------------------------------------------------------------------
@@ -286,13 +301,13 @@ template <int DT, bool Y16, int TOK, int U, bool PREFETCH_Y, bool SPLIT>
 __device__ __forceinline__ void expand_vec_body(const Item &it, const int32_t *__restrict__ pb,
                                                 const uint16_t *__restrict__ pool,
                                                 const int32_t *__restrict__ tok_idx, int H, int v_stride,
-                                                void *__restrict__ y, const float *__restrict__ v, int col, bool live,
-                                                float *red)
+                                                void *__restrict__ y, const float *v, int col, bool live,
+                                                float *red, int v_pos0 = -1)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = SPLIT ? (int)(threadIdx.x / kWave) : 0;
     constexpr int kStep = SPLIT ? kSplitWaves : 1;
-    const float *vrow = v + (int64_t)it.pos0 * v_stride;
+    const float *vrow = v + (int64_t)(v_pos0 < 0 ? it.pos0 : v_pos0) * v_stride; // row of v of the item's first token
     float acc[TOK][8];
 #pragma unroll
     for (int t = 0; t < TOK; ++t)
@@ -431,6 +446,62 @@ __global__ __launch_bounds__(kSplitWaves *kWave) void expand_vec_split_kernel(co
         expand_vec_body<DT, Y16, kExpandTok, 8, false, true>(it, pb, pool, tok_idx, H, v_stride, args.y[cs], args.v[cs], col, live, red);
 }
 
+
+// ---------------------------------------------------------------------------------------
+// decode path, both stages in ONE launch: a workgroup = one adapter group of at most kExpandTok
+// tokens, one wavefront per 512 columns of H.  First the wavefronts share out the adapter's A
+// pages and leave v = x*A in LDS (shrink_vec_core), then every wavefront walks the B pages for
+// its own columns (expand_vec_body) and updates y.  v never leaves the compute unit, x is staged
+// once per group instead of once per four pages, and a decode step is one kernel instead of
+// two dependent ones (each of which spends its first microseconds waiting for work items,
+// page lists and the first pages).  Used when a batch has enough such groups to fill the GPU
+// with whole-group workgroups (the scheduler decides); results are bit-identical to the two
+// kernels' - the same sums in the same order.
+// ---------------------------------------------------------------------------------------
+template <int DT, bool Y16, int U>
+__global__ __launch_bounds__(1024) void lora_vec_fused_kernel(const Item *__restrict__ items,
+                                                               const int32_t *__restrict__ arena,
+                                                               const uint16_t *__restrict__ pool,
+                                                               const int32_t *__restrict__ tok_idx, int H,
+                                                               int v_pad, MultiArgs args)
+{
+    extern __shared__ u32x4 smem[]; // x rows [kExpandTok][H/8], then v [kExpandTok][v_pad] floats
+    const int cs = blockIdx.x % args.n;
+    const Item it = items[blockIdx.x / args.n];
+    const uint16_t *__restrict__ x = static_cast<const uint16_t *>(args.x[cs]);
+    const int nch = H >> 3;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int nw = blockDim.x / kWave;
+    float *vl = reinterpret_cast<float *>(smem + (size_t)kExpandTok * nch);
+    const int32_t *pa = arena + it.arena_off + (int64_t)args.slot[cs] * 2 * it.rank;
+    shrink_vec_core<DT, U>(
+        pa, it.rank, it.ntok, wave, nw, lane, pool, H, smem,
+        [&]() {
+            for (int t = 0; t < it.ntok; ++t) {
+                const u32x4 *row = reinterpret_cast<const u32x4 *>(x + (int64_t)tok_idx[it.pos0 + t] * H);
+                for (int c = tid; c < nch; c += (int)blockDim.x) smem[t * nch + c] = row[c];
+            }
+            __syncthreads();
+        },
+        [&](int t, int j, float s) { vl[t * v_pad + j] = s; });
+    __syncthreads();
+    // expand: 512-column strips wave, wave + nw, ... (one strip per wavefront for H <= 8192)
+    const int32_t *pb = pa + it.rank;
+    for (int c0 = wave * 512; c0 < H; c0 += nw * 512) {
+        const int col = c0 + lane * 8;
+        const bool live = col < H;
+        Item strip = it;
+        strip.a = c0;   // lanes beyond H read the strip's first column and are dropped at the store
+        if (it.ntok == 1)
+            expand_vec_body<DT, Y16, 1, 8, true, false>(strip, pb, pool, tok_idx, H, v_pad, args.y[cs], vl, col, live, nullptr, 0);
+        else if (it.ntok == 2)
+            expand_vec_body<DT, Y16, 2, 8, true, false>(strip, pb, pool, tok_idx, H, v_pad, args.y[cs], vl, col, live, nullptr, 0);
+        else
+            expand_vec_body<DT, Y16, kExpandTok, 8, false, false>(strip, pb, pool, tok_idx, H, v_pad, args.y[cs], vl, col, live, nullptr, 0);
+    }
+}
 
 // ---------------------------------------------------------------------------------------
 // prefill path (MFMA).  Matrix blocks are 32 x 32 with 16 k-values per instruction
@@ -1209,18 +1280,70 @@ int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void 
     return check_launch("gather_pages");
 }
 
-int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream)
+// loads per block of the vector shrink: as few blocks per page as 8 loads allow, then the smallest U that fits
+static int shrink_loads_per_block(int H)
+{
+    const int per_lane = (H / 8 + kWave - 1) / kWave;
+    const int nblk = (per_lane + 7) / 8;
+    return std::max(4, (per_lane + nblk - 1) / nblk);
+}
+
+int32_t launch_fused(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16)
+{
+    slora_pool *pool = plan->pool;
+    if (plan->vf_items.empty()) return SLORA_OK;
+    const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
+    hipStream_t st = (hipStream_t)stream;
+    const int H = pool->H;
+    const int strips = (H + 511) / 512;
+    const dim3 block((unsigned)(std::min(strips, 16) * kWave));
+    const dim3 grid((unsigned)(plan->vf_items.size() * (size_t)n));
+    const int v_pad = plan->v_stride;
+    const size_t lds = (size_t)kExpandTok * H * 2 + (size_t)kExpandTok * v_pad * sizeof(float);
+    const int U = shrink_loads_per_block(H);
+    // more than 64 KiB of dynamic LDS (H = 8192) has to be allowed once per kernel instance
+    hipError_t attr = hipSuccess;
+#define SLORA_FUSED(DT, Y, UU)                                                                                       \
+    {                                                                                                                \
+        static bool allowed = false;                                                                                 \
+        if (!allowed && lds > 65536) {                                                                               \
+            attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&lora_vec_fused_kernel<DT, Y, UU>),           \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);                      \
+            allowed = attr == hipSuccess;                                                                            \
+        }                                                                                                            \
+        if (attr == hipSuccess)                                                                                      \
+            hipLaunchKernelGGL((lora_vec_fused_kernel<DT, Y, UU>), grid, block, lds, st, plan->d_vf, pool->d_arena, \
+                               base, plan->d_tok_idx, H, v_pad, args);                                               \
+    }
+#define SLORA_FUSED_U(DT, Y)                      \
+    switch (U) {                                  \
+    case 4: SLORA_FUSED(DT, Y, 4); break;         \
+    case 5: SLORA_FUSED(DT, Y, 5); break;         \
+    case 6: SLORA_FUSED(DT, Y, 6); break;         \
+    case 7: SLORA_FUSED(DT, Y, 7); break;         \
+    default: SLORA_FUSED(DT, Y, 8); break;        \
+    }
+    if (pool->dtype == SLORA_F16) {
+        if (y16) { SLORA_FUSED_U(SLORA_F16, true) } else { SLORA_FUSED_U(SLORA_F16, false) }
+    } else {
+        if (y16) { SLORA_FUSED_U(SLORA_BF16, true) } else { SLORA_FUSED_U(SLORA_BF16, false) }
+    }
+#undef SLORA_FUSED_U
+#undef SLORA_FUSED
+    if (attr != hipSuccess) return fail(SLORA_EHIP, "hipFuncSetAttribute(LDS size): %s", hipGetErrorString(attr));
+    return check_launch("lora_vec_fused");
+}
+
+int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool heads_only)
 {
     slora_pool *pool = plan->pool;
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
     hipStream_t st = (hipStream_t)stream;
-    if (!plan->vs_items.empty()) {
-        const dim3 grid((unsigned)(plan->vs_items.size() * (size_t)n));
+    const size_t n_vs = heads_only ? (size_t)plan->n_vs_head : plan->vs_items.size();
+    if (n_vs > 0) {
+        const dim3 grid((unsigned)(n_vs * (size_t)n));
         const size_t lds = (size_t)plan->max_shrink_tok * pool->H * 2;
-        // loads per block: as few blocks per page as 8 loads allow, then the smallest U that fits
-        const int per_lane = (pool->H / 8 + kWave - 1) / kWave;
-        const int nblk = (per_lane + 7) / 8;
-        const int U = std::max(4, (per_lane + nblk - 1) / nblk);
+        const int U = shrink_loads_per_block(pool->H);
 #define SLORA_LAUNCH_SHRINK(DT, UU)                                                                              \
     hipLaunchKernelGGL((shrink_vec_kernel<DT, UU>), grid, dim3(kShrinkThreads), lds, st, plan->d_vs, pool->d_arena, \
                        base, plan->d_tok_idx, pool->H, plan->v_stride, args)
@@ -1271,7 +1394,7 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *
     return SLORA_OK;
 }
 
-int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16)
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16, bool heads_only)
 {
     slora_pool *pool = plan->pool;
     const uint16_t *base = static_cast<const uint16_t *>(pool->dev_base);
@@ -1280,8 +1403,9 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *
 #define SLORA_PICK(KERNEL)                                                                   \
     (pool->dtype == SLORA_F16 ? (y16 ? KERNEL<SLORA_F16, true> : KERNEL<SLORA_F16, false>)   \
                               : (y16 ? KERNEL<SLORA_BF16, true> : KERNEL<SLORA_BF16, false>))
-    if (!plan->ve_items.empty()) {
-        const dim3 grid((unsigned)(plan->ve_items.size() * (size_t)n));
+    const size_t n_ve = heads_only ? (size_t)plan->n_ve_head : plan->ve_items.size();
+    if (n_ve > 0) {
+        const dim3 grid((unsigned)(n_ve * (size_t)n));
         if (plan->expand_split)
             hipLaunchKernelGGL(SLORA_PICK(expand_vec_split_kernel), grid, dim3(kSplitWaves * kWave), 0, st, plan->d_ve,
                                pool->d_arena, base, plan->d_tok_idx, pool->H, plan->v_stride, args);

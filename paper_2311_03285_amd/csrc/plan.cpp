@@ -169,7 +169,28 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         plan->expand_split = ecols == 512 && (int64_t)n_vec_groups * chunks < 512;
         // the vector shrink stages its tokens' x rows in LDS: at most 64 KiB of them per item
         const int32_t shrink_tok = std::max(1, std::min(kShrinkTok, 65536 / (H * 2)));
+        const int32_t shrink_pages = (int32_t)pool->shrink_pages;
         plan->expand_threads = ecols / 8;
+        // One launch for both stages of decode groups (at most kExpandTok tokens): a workgroup per
+        // group streams the whole adapter.  That pays when the batch has enough groups to fill
+        // the GPU about three times over with whole-group workgroups AND the groups are large
+        // (a workgroup's waits for its work item, page lists and first pages are then short beside
+        // its streaming): measured per step, 2.39 -> 2.27 ms on the mixed configuration (H = 8192,
+        // 2.3 MB of pages per group), 111 -> 113 us on the large-pool decode one (0.6 MB per group).
+        // x rows are staged in LDS (64 KiB: H <= 8192).
+        int64_t n_small = 0, small_bytes = 0;
+        for (int32_t gi : order) {
+            const int64_t n = (int64_t)groups[(size_t)gi].toks.size();
+            if (n < min_tokens && n <= kExpandTok) {
+                n_small++;
+                small_bytes += (int64_t)groups[(size_t)gi].rank * H * 4; // A and B pages
+            }
+        }
+        const bool fuse = pool->fuse_decode != 0 && H <= 8192 &&
+                          (pool->fuse_decode > 1 ||
+                           (n_small * launch_slots >= 3 * 256 && small_bytes >= n_small * (int64_t(1) << 20)));
+        std::vector<Item> vs_tail, ve_tail;
+        plan->vf_items.clear();
         for (int32_t gi : order) {
             const Group &g = groups[(size_t)gi];
             const int32_t n = (int32_t)g.toks.size();
@@ -236,20 +257,29 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
                 }
             } else {
                 plan->n_groups_vec++;
+                // a group the one-launch decode kernel can take goes to the end of the two lists
+                // (the two-stage calls run the whole lists, a fused apply only their heads)
+                const bool fused = fuse && n <= kExpandTok;
+                std::vector<Item> &vs = fused ? vs_tail : plan->vs_items;
+                std::vector<Item> &ve = fused ? ve_tail : plan->ve_items;
+                if (fused) plan->vf_items.push_back(Item{off, g.rank, 0, H, pos_base, n, 0, 0});
                 for (int32_t p = 0; p < n; p += shrink_tok) {
                     const int32_t nt = std::min(shrink_tok, n - p);
                     plan->max_shrink_tok = std::max(plan->max_shrink_tok, nt);
-                    for (int32_t j = 0; j < g.rank; j += kShrinkPages)
-                        plan->vs_items.push_back(
-                            Item{off, g.rank, j, std::min(kShrinkPages, g.rank - j), pos_base + p, nt, 0, 0});
+                    for (int32_t j = 0; j < g.rank; j += shrink_pages)
+                        vs.push_back(Item{off, g.rank, j, std::min(shrink_pages, g.rank - j), pos_base + p, nt, 0, 0});
                 }
                 for (int32_t p = 0; p < n; p += kExpandTok) {
                     const int32_t nt = std::min(kExpandTok, n - p);
                     for (int32_t c = 0; c < H; c += ecols)
-                        plan->ve_items.push_back(Item{off, g.rank, c, std::min(ecols, H - c), pos_base + p, nt, 0, 0});
+                        ve.push_back(Item{off, g.rank, c, std::min(ecols, H - c), pos_base + p, nt, 0, 0});
                 }
             }
         }
+        plan->n_vs_head = (int32_t)plan->vs_items.size();
+        plan->n_ve_head = (int32_t)plan->ve_items.size();
+        plan->vs_items.insert(plan->vs_items.end(), vs_tail.begin(), vs_tail.end());
+        plan->ve_items.insert(plan->ve_items.end(), ve_tail.begin(), ve_tail.end());
         // longest first: the hardware hands a workgroup to a compute unit as one becomes free, so
         // with the big shares at the head of the list and the small ones at its end the launch
         // ends on every unit at about the same time
@@ -273,7 +303,7 @@ int32_t slora_plan::upload()
     if (n_tok == 0) return SLORA_OK;
     const size_t tok_bytes = (n_tok * sizeof(int32_t) + 63) / 64 * 64;
     const size_t bytes = tok_bytes + (ms_items.size() + mj_items.size()) * sizeof(MsItem) +
-                         (vs_items.size() + ve_items.size() + me_items.size()) * sizeof(Item);
+                         (vs_items.size() + ve_items.size() + me_items.size() + vf_items.size()) * sizeof(Item);
     // The image is assembled in the pinned half of a recycled buffer set and copied to the
     // device half on the pool's own upload stream: the copy runs beside whatever the caller's
     // streams are doing, and the first launch of the plan waits for it through an event.
@@ -292,6 +322,7 @@ int32_t slora_plan::upload()
     put(vs_items);
     put(ve_items);
     put(me_items);
+    put(vf_items);
     void *up_v = nullptr;
     rc = pool->uploads(&up_v);
     if (rc != SLORA_OK) {
@@ -316,6 +347,7 @@ int32_t slora_plan::upload()
     d_vs = (Item *)(d_mj + mj_items.size());
     d_ve = d_vs + vs_items.size();
     d_me = d_ve + ve_items.size();
+    d_vf = d_me + me_items.size();
     return SLORA_OK;
 }
 
@@ -357,8 +389,10 @@ int32_t check_plan(slora_plan *plan, int32_t n, const int32_t *slots)
 }
 
 // scratch: where v goes; NULL = the plan's own buffer (grown on demand)
+// y != NULL: part of an apply - decode groups the plan marked for it run both stages in one
+// launch here, and the two-stage launches (here and in do_expand) cover the other groups only
 int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void *const *x, void *stream,
-                  float *scratch = nullptr)
+                  float *scratch = nullptr, void *const *y = nullptr, bool y16 = false)
 {
     if (!x) return fail(SLORA_EINVAL, "x is NULL");
     if (plan->T_act == 0) return SLORA_OK;
@@ -382,10 +416,17 @@ int32_t do_shrink(slora_plan *plan, int32_t n, const int32_t *slots, const void 
     if (rc == SLORA_OK) rc = plan->enter(stream);
     if (rc != SLORA_OK) return rc;
     plan->fill_args(a, n, v);
-    rc = launch_shrink(plan, n, a, stream);
+    const bool fused = y != nullptr && !plan->vf_items.empty();
+    if (fused) {
+        for (int32_t k = 0; k < n; ++k) a.y[k] = y[k];
+        rc = launch_fused(plan, n, a, stream, y16);
+        if (rc != SLORA_OK) return rc;
+    }
+    rc = launch_shrink(plan, n, a, stream, fused);
     if (rc == SLORA_OK) {
         plan->v_slots = n;
         plan->v_used = v;
+        plan->v_complete = !fused; // after a fused apply the v of the fused groups never reached memory
     }
     return rc;
 }
@@ -402,7 +443,8 @@ int32_t check_y(int32_t n, void *const *y)
     return SLORA_OK;
 }
 
-int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const *y, void *stream, bool y16)
+int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const *y, void *stream, bool y16,
+                  bool after_fused = false)
 {
     int32_t rc = check_y(n, y);
     if (rc != SLORA_OK) return rc;
@@ -413,14 +455,14 @@ int32_t do_expand(slora_plan *plan, int32_t n, const int32_t *slots, void *const
         a.y[k] = y[k];
         a.slot[k] = slots[k];
     }
-    if (plan->v_slots != n || !plan->v_used)
-        return fail(SLORA_EINVAL, "expand of %d slot(s) needs a preceding shrink of %d slot(s)", n, n);
+    if (plan->v_slots != n || !plan->v_used || (!after_fused && !plan->v_complete))
+        return fail(SLORA_EINVAL, "expand of %d slot(s) needs a preceding slora_lora_shrink of %d slot(s)", n, n);
     DeviceScope dev(plan->pool->device);
     if (dev.status() != SLORA_OK) return dev.status();
     rc = plan->enter(stream);
     if (rc != SLORA_OK) return rc;
     plan->fill_args(a, n, plan->v_used);
-    return launch_expand(plan, n, a, stream, y16);
+    return launch_expand(plan, n, a, stream, y16, after_fused && !plan->vf_items.empty());
 }
 
 } // namespace
@@ -490,7 +532,8 @@ int32_t slora_plan_info(const slora_plan *plan, int64_t *out, int32_t n)
                                           plan->v_stride,
                                           plan->sum_rank,
                                           plan->n_sync,
-                                          plan->v_slot_floats(plan->pool->dtype) * (int64_t)sizeof(float)};
+                                          plan->v_slot_floats(plan->pool->dtype) * (int64_t)sizeof(float),
+                                          (int64_t)plan->vf_items.size()};
     for (int32_t k = 0; k < n; ++k) out[k] = v[k];
     return SLORA_OK;
 }
@@ -536,9 +579,9 @@ int32_t apply_multi(slora_plan *plan, int32_t n, const int32_t *slots, const voi
         scratch = static_cast<float *>(plan->pool->static_scratch);
         if (!scratch) return fail(SLORA_EHIP, "the static scratch was not resolved for this pool's device");
     }
-    rc = do_shrink(plan, n, slots, x, stream, scratch);
+    rc = do_shrink(plan, n, slots, x, stream, scratch, y, y16);
     if (rc != SLORA_OK) return rc;
-    return do_expand(plan, n, slots, y, stream, y16);
+    return do_expand(plan, n, slots, y, stream, y16, true);
 }
 } // namespace
 

@@ -666,6 +666,16 @@ int32_t slora_set_option(slora_pool *pool, const char *key, int64_t value)
         pool->mfma_split_min_h = value;
         return SLORA_OK;
     }
+    if (!std::strcmp(key, "fuse_decode")) {
+        if (value < 0 || value > 2) return fail(SLORA_EINVAL, "fuse_decode must be 0, 1 or 2");
+        pool->fuse_decode = value;
+        return SLORA_OK;
+    }
+    if (!std::strcmp(key, "shrink_pages")) {
+        if (value < 1 || value > 1024) return fail(SLORA_EINVAL, "shrink_pages must be in [1, 1024]");
+        pool->shrink_pages = value;
+        return SLORA_OK;
+    }
     if (!std::strcmp(key, "upload_groups")) {
         if (value < 1 || value > 65535) return fail(SLORA_EINVAL, "upload_groups must be in [1, 65535]");
         pool->upload_groups = value;

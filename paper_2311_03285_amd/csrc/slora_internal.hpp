@@ -69,7 +69,6 @@ struct MultiArgs {
 
 // Tile constants the scheduler and the kernels must agree on.
 constexpr int kShrinkTok = 4;     // tokens per vector-shrink item (x rows staged in LDS)
-constexpr int kShrinkPages = 4;   // pages per vector-shrink item
 constexpr int kExpandTok = 4;     // tokens per vector-expand item (accumulators in registers)
 constexpr int kExpandColsMax = 1024; // most columns per vector-expand item (a multiple of 512, <= 4096; measured best on cfg4: 1024)
 constexpr int kMfmaTok = 32;      // tokens per v tile = per MFMA-expand item (one 32-row MFMA block)
@@ -148,6 +147,8 @@ struct slora_pool {
     int64_t mfma_min_tiles = 32;
     int64_t xcd_group = 0;                            // bit 0: MFMA shrink list grouped per XCD, bit 1: expand list
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
+    int64_t fuse_decode = 1;                          // 0: never, 1: when the batch has enough small groups, 2: always
+    int64_t shrink_pages = 4;                         // pages of A per vector-shrink item (its x rows are staged once for all of them)
     int64_t mfma_split_bytes = 256 << 10;             // MFMA shrink: a tile's H range is cut into shares of about this many row bytes
     int64_t mfma_split_min_h = 1024;                  // ... but no share is shorter than this many elements of H
 
@@ -187,6 +188,8 @@ struct slora_plan {
     // host image
     std::vector<int32_t> tok_idx;                     // sorted position -> token index
     std::vector<slora::Item> vs_items, ve_items, me_items;
+    std::vector<slora::Item> vf_items; // decode groups for the one-launch kernel (their two-stage items end vs / ve)
+    int32_t n_vs_head = 0, n_ve_head = 0; // items of vs / ve that belong to other groups
     std::vector<slora::MsItem> ms_items;
     std::vector<slora::MsItem> mj_items; // one record per split tile, for the kernel that joins the shares
     int32_t ms_max_nj = 0;     // most ranks in one MFMA shrink item (sizes the kernel's LDS)
@@ -197,7 +200,7 @@ struct slora_plan {
     // device image: tok_idx and the four lists in one buffer of the plan's buffer set
     slora::Buffers *set = nullptr;
     int32_t *d_tok_idx = nullptr;
-    slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_me = nullptr;
+    slora::Item *d_vs = nullptr, *d_ve = nullptr, *d_me = nullptr, *d_vf = nullptr;
     slora::MsItem *d_ms = nullptr, *d_mj = nullptr;
 
     // scratch for v = x*A (set->v, or the library's static scratch), per slot: T_act * v_stride floats (vector path rows), n_mfma_tiles * (v_stride/16) *
@@ -215,6 +218,7 @@ struct slora_plan {
     int64_t v_total_floats(int32_t n, int32_t dtype) const { return (int64_t)n * v_slot_floats(dtype); }
     float *v_used = nullptr; // where the latest shrink left v
     int32_t v_slots = 0;     // n of the latest shrink
+    bool v_complete = false; // the latest shrink left v for every group (not so after an apply that fused decode groups)
 
     // Stream order.  Every launch of a plan reads its work lists and reads or writes its v, so
     // all of a plan's work is kept in ONE order: when a call names another stream than the
@@ -238,7 +242,9 @@ int32_t launch_write_pages(slora_pool *pool, const int32_t *d_idx, int64_t n, co
                            void *stream, int32_t max_groups = 0); // max_groups > 0 caps the grid
 int32_t launch_gather(slora_pool *pool, int64_t arena_entry, int32_t rank, void *dev_out, void *stream);
 int32_t static_scratch_address(int device, void **out); // `device` must be current
-int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream);
-int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16);
+// heads_only: the vector lists without the groups that launch_fused has served
+int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool heads_only = false);
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16, bool heads_only = false);
+int32_t launch_fused(slora_plan *plan, int32_t n, const MultiArgs &args, void *stream, bool y16);
 
 } // namespace slora

@@ -17,11 +17,11 @@ F16, BF16 = 0, 1
 OK, EINVAL, ERANGE, EBUSY, ENOENT, ESEG, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
 MAX_MULTI = 8
 STATIC_SCRATCH_BYTES = 64 << 20
-PLAN_INFO_N = 12
+PLAN_INFO_N = 13
 POOL_STATS_N = 3
 PLAN_INFO_KEYS = ("tokens", "groups", "groups_vec", "groups_mfma", "vec_shrink_items", "vec_expand_items",
                   "mfma_shrink_items", "mfma_expand_items", "v_stride", "sum_rank", "split_tiles",
-                  "scratch_bytes_per_slot")
+                  "scratch_bytes_per_slot", "groups_fused")
 
 LIB_PATH = os.environ.get("SLORA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libslora_hip.so")
 _lib = None

@@ -116,7 +116,7 @@ static void check_tokens(const slora_plan *plan, int32_t pos0, int32_t ntok)
     }
 }
 
-int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &a, void *)
+int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &a, void *, bool heads_only)
 {
     const slora_pool *pool = plan->pool;
     const int32_t np = pool->dtype == SLORA_F16 ? 2 : 3;
@@ -126,12 +126,13 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &a, void *)
     for (int32_t k = 0; k < n; ++k) {
         REQUIRE(a.x[k] && a.v[k]);
         float *v = a.v[k];
-        for (size_t i = 0; i < plan->vs_items.size(); ++i) {
+        REQUIRE(plan->n_vs_head >= 0 && (size_t)plan->n_vs_head <= plan->vs_items.size());
+        for (size_t i = 0; i < (heads_only ? (size_t)plan->n_vs_head : plan->vs_items.size()); ++i) {
             const Item &it = plan->d_vs[i];
             REQUIRE(std::memcmp(&it, &plan->vs_items[i], sizeof it) == 0);
             check_pages(plan, it.arena_off, it.rank, a.slot[k]);
             check_tokens(plan, it.pos0, it.ntok);
-            REQUIRE(it.ntok <= kShrinkTok && it.a >= 0 && it.b > 0 && it.b <= kShrinkPages && it.a + it.b <= it.rank);
+            REQUIRE(it.ntok <= kShrinkTok && it.a >= 0 && it.b > 0 && it.b <= pool->shrink_pages && it.a + it.b <= it.rank);
             for (int32_t t = 0; t < it.ntok; ++t)
                 for (int32_t j = it.a; j < it.a + it.b; ++j) v[(int64_t)(it.pos0 + t) * plan->v_stride + j] = 0.f;
         }
@@ -170,13 +171,14 @@ int32_t launch_shrink(slora_plan *plan, int32_t n, const MultiArgs &a, void *)
     return SLORA_OK;
 }
 
-int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &a, void *, bool)
+int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &a, void *, bool, bool heads_only)
 {
     const slora_pool *pool = plan->pool;
     REQUIRE(a.n == n);
     for (int32_t k = 0; k < n; ++k) {
         REQUIRE(a.y[k] && a.v[k]);
-        for (size_t i = 0; i < plan->ve_items.size(); ++i) {
+        REQUIRE(plan->n_ve_head >= 0 && (size_t)plan->n_ve_head <= plan->ve_items.size());
+        for (size_t i = 0; i < (heads_only ? (size_t)plan->n_ve_head : plan->ve_items.size()); ++i) {
             const Item &it = plan->d_ve[i];
             REQUIRE(std::memcmp(&it, &plan->ve_items[i], sizeof it) == 0);
             check_pages(plan, it.arena_off, it.rank, a.slot[k]);
@@ -194,6 +196,31 @@ int32_t launch_expand(slora_plan *plan, int32_t n, const MultiArgs &a, void *, b
             REQUIRE(it.tile >= 0 && it.tile < plan->n_mfma_tiles);
         }
     }
+    return SLORA_OK;
+}
+
+int32_t launch_fused(slora_plan *plan, int32_t n, const MultiArgs &a, void *, bool)
+{
+    const slora_pool *pool = plan->pool;
+    REQUIRE(a.n == n && pool->H <= 8192);
+    // every fused group is a whole group of at most kExpandTok tokens, and the tails of the two
+    // vector lists are exactly these groups' two-stage items
+    std::set<int32_t> fused_pos;
+    for (size_t i = 0; i < plan->vf_items.size(); ++i) {
+        const Item &it = plan->d_vf[i];
+        REQUIRE(std::memcmp(&it, &plan->vf_items[i], sizeof it) == 0);
+        REQUIRE(it.ntok >= 1 && it.ntok <= kExpandTok && it.rank <= plan->v_stride);
+        check_tokens(plan, it.pos0, it.ntok);
+        for (int32_t k = 0; k < n; ++k) {
+            REQUIRE(a.x[k] && a.y[k]);
+            check_pages(plan, it.arena_off, it.rank, a.slot[k]);
+        }
+        fused_pos.insert(it.pos0);
+    }
+    for (size_t i = 0; i < plan->vs_items.size(); ++i)
+        REQUIRE((fused_pos.count(plan->vs_items[i].pos0) != 0) == (i >= (size_t)plan->n_vs_head));
+    for (size_t i = 0; i < plan->ve_items.size(); ++i)
+        REQUIRE((fused_pos.count(plan->ve_items[i].pos0) != 0) == (i >= (size_t)plan->n_ve_head));
     return SLORA_OK;
 }
 
@@ -221,6 +248,8 @@ int main(int argc, char **argv)
         REQUIRE(slora_set_option(pool, "mfma_split_bytes", 4096 << rnd(0, 6)) == SLORA_OK);
         REQUIRE(slora_set_option(pool, "mfma_split_min_h", 128 << rnd(0, 3)) == SLORA_OK);
         REQUIRE(slora_set_option(pool, "xcd_group", rnd(0, 3)) == SLORA_OK);
+        REQUIRE(slora_set_option(pool, "shrink_pages", rnd(1, 12)) == SLORA_OK);
+        REQUIRE(slora_set_option(pool, "fuse_decode", rnd(0, 2)) == SLORA_OK);
         std::vector<int32_t> loaded;
         std::vector<slora_plan *> plans;
         std::vector<uint16_t> x((size_t)4096 * H, 0x3800), w;

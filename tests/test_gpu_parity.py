@@ -378,3 +378,62 @@ def test_random_shapes_against_the_oracle(seed):
         ref = oracle_slot(w, 0, y_in=dec(w.y16_bits(0)).astype(np.float32))
         tol = (2.0 ** -10 if dtype == synth.F16 else 2.0 ** -7) * np.maximum(np.abs(ref), 2.0 ** -14) + 1e-5
         assert np.all(np.abs(dec(got16) - ref) <= tol)
+
+
+# ------------------------------------------------------------------ decode groups in one launch
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+@pytest.mark.parametrize("H", [64, 1000, 5120, 6656, 8192])
+def test_one_launch_decode_kernel_beside_the_two_kernels(dtype, H):
+    """Adapter groups of at most four tokens through the kernel that does both stages in one
+    launch (forced) against the two-kernel path on the same inputs (equal up to the order in
+    which the small-batch expand adds its rank blocks), fp32 y and 16-bit y, several slots per
+    launch, the entry point without allocation; and against the oracle."""
+    w = ragged_workload(1300 + H, dtype, H=H, n_slots=3, n_pages=900)
+    with DeviceWorkload(w, real_adapters="all") as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY)
+        outs = {}
+        for mode in (0, 2):
+            slora.set_option(dw.pool, "fuse_decode", mode)
+            plan = dw.plan(seg_offsets=None)
+            info = slora.plan_info(plan)
+            assert (info["groups_fused"] > 0) == (mode == 2)
+            assert info["groups_fused"] < info["groups"]          # the nine-token group stays on two kernels
+            xs = [dw.x_dev(s) for s in range(3)]
+            ys = [dw.y_dev(s) for s in range(3)]
+            y16 = [bits_to_device(w.y16_bits(s), dw.device) for s in range(3)]
+            slora.lora_apply_multi(plan, [0, 1, 2], [t.data_ptr() for t in xs], [t.data_ptr() for t in ys])
+            slora.lora_apply_multi_y16(plan, [2, 0], [xs[2].data_ptr(), xs[0].data_ptr()],
+                                       [y16[2].data_ptr(), y16[0].data_ptr()])
+            st = dw.y_dev(1)
+            slora.lora_apply_multi_static(plan, [1], [xs[1].data_ptr()], [st.data_ptr()])
+            torch.cuda.synchronize()
+            outs[mode] = ([t.cpu().numpy() for t in ys], [t.cpu().numpy() for t in y16], st.cpu().numpy())
+            if mode == 2:       # v of the fused groups never reached memory: an expand alone is refused
+                with pytest.raises(slora.SloraError) as e:
+                    slora.lora_expand(plan, [1], [st.data_ptr()])
+                assert e.value.code == slora.EINVAL
+                slora.lora_shrink(plan, [1], [xs[1].data_ptr()])
+                st2 = dw.y_dev(1)
+                slora.lora_expand(plan, [1], [st2.data_ptr()])
+                torch.cuda.synchronize()
+                assert np.array_equal(st2.cpu().numpy(), outs[0][2])      # the two stages: the two-kernel bits
+        for s in range(3):
+            rel, _ = errors(outs[2][0][s], outs[0][0][s].astype(np.float64))
+            assert rel <= 1e-6, (s, rel)
+            differ = np.mean(outs[0][1][s] != outs[2][1][s])              # 16-bit y: the same rounding nearly everywhere
+            assert differ <= 1e-3, (s, differ)
+            rel, _ = assert_close(outs[2][0][s], oracle_slot(w, s), f"one-launch decode, slot {s}")
+            assert rel <= REL_L2_EXPECTED
+        assert np.array_equal(outs[2][2], outs[2][0][1])                  # static scratch entry: the same kernel
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_one_launch_decode_kernel_integer_inputs_bit_exact(dtype):
+    w = ragged_workload(1400, dtype, H=5120, n_pages=900, int_valued=True)
+    with DeviceWorkload(w, real_adapters="all") as dw:
+        slora.set_option(dw.pool, "mfma_min_tokens", VEC_ONLY)
+        slora.set_option(dw.pool, "fuse_decode", 2)
+        plan = dw.plan(seg_offsets=None)
+        assert slora.plan_info(plan)["groups_fused"] > 0
+        for slot in range(w.n_slots):
+            assert np.array_equal(gpu_slot(dw, slot, plan).astype(np.float64), oracle_slot(w, slot))
