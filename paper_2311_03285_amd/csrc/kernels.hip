@@ -1015,6 +1015,10 @@ __global__ __launch_bounds__(kMfmaThreads) void join_shares_kernel(const MsItem 
 // stored.
 // ---------------------------------------------------------------------------------------
 constexpr int kSlabStride = 20; // dwords per column in LDS: 16 (32 ranks) + 4 pad, keeps 16-byte alignment
+constexpr int kSlabGroupPad = 8; // extra dwords before every 8 columns: the 8 column groups a transposing store
+                                 // touches then fall into different banks (8 x 20 dwords alone is a multiple of 32:
+                                 // rocprofv3 counted bank conflicts on 58 % of this kernel's LDS cycles)
+__device__ __forceinline__ int slab_col(int c) { return c * kSlabStride + (c >> 3) * kSlabGroupPad; }
 // The y tile of a wavefront (32 rows x 64 columns) is staged in the same slab; padded rows keep the
 // 16-byte alignment and spread the accumulator-layout accesses over the banks.
 template <bool Y16>
@@ -1031,7 +1035,7 @@ struct YTile<false> {
     static constexpr int stride = 68;                  // 272-byte rows
     static constexpr int bytes = 32 * stride * 4;
 };
-constexpr int kSlabBytes = 64 * kSlabStride * 4;
+constexpr int kSlabBytes = (64 * kSlabStride + 8 * kSlabGroupPad) * 4;
 
 template <int DT, bool Y16>
 __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item *__restrict__ items,
@@ -1168,7 +1172,7 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
-            uint32_t *dst = slab + (8 * cg) * kSlabStride + 8 * rd + kp;
+            uint32_t *dst = slab + slab_col(8 * cg) + 8 * rd + kp; // columns 8 cg .. 8 cg + 7: one group, same pad
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 dst[(2 * e) * kSlabStride] = (wa[rd][e] & 0xffffu) | (wb[rd][e] << 16);
@@ -1184,7 +1188,7 @@ __global__ __launch_bounds__(kMfmaThreads, 4) void expand_mfma_kernel(const Item
             u32x4 bop[2];
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
-                bop[nb] = *reinterpret_cast<const u32x4 *>(slab + (nb * 32 + n) * kSlabStride + 8 * s + 4 * q);
+                bop[nb] = *reinterpret_cast<const u32x4 *>(slab + slab_col(nb * 32 + n) + 8 * s + 4 * q);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
 #pragma unroll

@@ -152,3 +152,52 @@ def test_scheduler_groups_buckets_and_routes():
     assert slora.plan_info(plan)["groups_mfma"] == 0
     slora.plan_destroy(plan)
     slora.pool_destroy(p)
+
+
+def test_scheduler_shares_of_H_and_one_launch_decode_groups():
+    """MFMA shrink tiles of 128 tokens x 128 ranks whose H range is handed to several workgroups,
+    and the rule that sends decode groups to the one-launch kernel."""
+    p = mk(H=4096, n_pages=1 << 15, max_rank=256, n_slots=4)
+    at = 0
+    for a, r in {0: 128, 1: 200, 2: 8}.items():
+        slora.adapter_load(p, a, r, np.arange(at, at + 8 * r))
+        at += 8 * r
+    slora.set_option(p, "mfma_min_tiles", 1)
+    ids = [0] * 300 + [1] * 130 + [2] * 20
+    seg = [0, 300, 430, 450]
+    plan = slora.batch_plan(p, ids, seg)
+    info = slora.plan_info(plan)
+    assert info["groups_mfma"] == 3 and info["v_stride"] == 224
+    # tiles: adapter 0: 3 token tiles x 1 rank block; adapter 1: 2 x 2; adapter 2: 1 x 1
+    whole = 3 + 4 + 1
+    assert info["split_tiles"] >= 3 + 4 - 1 and info["mfma_shrink_items"] > whole
+    assert info["mfma_expand_items"] == (10 + 5 + 1) * (4096 // 256)
+    slora.plan_destroy(plan)
+    slora.set_option(p, "mfma_split_bytes", 1 << 30)          # shares as large as any tile: nothing is split
+    plan = slora.batch_plan(p, ids, seg)
+    info = slora.plan_info(plan)
+    assert info["split_tiles"] == 0 and info["mfma_shrink_items"] == whole
+    slora.plan_destroy(plan)
+    assert code(slora.set_option, p, "mfma_split_bytes", 100) == slora.EINVAL
+    assert code(slora.set_option, p, "mfma_split_min_h", 64) == slora.EINVAL
+    assert code(slora.set_option, p, "fuse_decode", 3) == slora.EINVAL
+    assert code(slora.set_option, p, "shrink_pages", 0) == slora.EINVAL
+    # decode groups: forced into the one-launch kernel, or not; never a group of more than 4 tokens
+    dec = [0, 1, 2, 1, 0, 0, 0, 0]                            # adapter 0: five tokens
+    for mode, want in ((0, 0), (1, 0), (2, 2)):
+        slora.set_option(p, "fuse_decode", mode)
+        plan = slora.batch_plan(p, dec)
+        assert slora.plan_info(plan)["groups_fused"] == want, mode
+        slora.plan_destroy(plan)
+    slora.pool_destroy(p)
+    # the default rule: enough small groups to fill the GPU, and large ones (>= 1 MiB of pages each)
+    p = mk(H=8192, n_pages=1 << 17, max_rank=64, n_slots=8)
+    for a in range(120):
+        slora.adapter_load(p, a, 64, np.arange(a * 1024, (a + 1) * 1024))
+    plan = slora.batch_plan(p, list(range(120)))              # 120 groups x 8 slots of 2 MiB each
+    assert slora.plan_info(plan)["groups_fused"] == 120
+    slora.plan_destroy(plan)
+    plan = slora.batch_plan(p, list(range(60)))               # too few to fill the GPU
+    assert slora.plan_info(plan)["groups_fused"] == 0
+    slora.plan_destroy(plan)
+    slora.pool_destroy(p)
