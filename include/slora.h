@@ -308,7 +308,7 @@ int32_t slora_lora_shrink_expand(slora_pool *pool, int32_t slot, const void *x,
  *                      and run faster on the vector kernels)
  *   "mfma_split_bytes" the MFMA shrink hands the H range of a tile (up to 128 tokens x up to 128 ranks)
  *                      to several workgroups, each taking about this many bytes of x and page rows
- *                      (default 262144); their partial sums are added in a fixed order by a small
+ *                      (default 1 MiB); their partial sums are added in a fixed order by a small
  *                      second kernel
  *   "mfma_split_min_h" ... but no share of H is shorter than this many elements (default 1024, at
  *                      least 128), so that the partial sums stay small beside the rows

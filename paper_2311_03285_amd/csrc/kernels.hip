@@ -742,7 +742,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
                                                  const uint16_t *__restrict__ pool,
                                                  const int32_t *__restrict__ tok_idx, int H, int v_stride,
                                                  uint16_t *__restrict__ vfrag, int8_t *__restrict__ vexp,
-                                                 float *__restrict__ partial, unsigned char *lds)
+                                                 float *__restrict__ partial, unsigned char *lds, int args_n)
 {
     constexpr int kLoads = MB + NB;                 // 16-byte loads per thread and chunk
     constexpr int kRows = 32 * (MB + NB);           // LDS rows of one buffer
@@ -776,8 +776,18 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
     struct Regs {
         u32x4 w[2][kLoads];
     };
-    auto load = [&](int g, Regs &r) { // granule g of the share (clamped to its last one), bytes clamped into the row
-        const int gg = it.c0 + min(g, n_gran - 1);
+    // Every workgroup starts its sweep over the share at another granule and wraps around: tiles
+    // launched together would otherwise walk H in lockstep, all of them asking the same few memory
+    // channels for the same column offset of their rows at the same time (a load-only probe of
+    // this access pattern: 4.5 TB/s in lockstep, 5.5 TB/s with staggered starts).  The order of a
+    // sum over H changes with it, its value only in the rounding.
+    const int g_first = (int)(((blockIdx.x / (unsigned)args_n) * 5u) % (unsigned)n_gran); // by item: every slot of a launch, and a launch of any number of slots, adds in the same order
+    auto granule = [&](int g) { // position in H of the share's g-th granule in this workgroup's order
+        const int k = min(g, n_gran - 1) + g_first;
+        return it.c0 + (k < n_gran ? k : k - n_gran);
+    };
+    auto load = [&](int g, Regs &r) { // g-th granule of the share (clamped to the last one), bytes clamped into the row
+        const int gg = granule(g);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int64_t off = min((int64_t)gg * kMsGranuleBytes + h * kMsRowBytes + cb, row_bytes - 16);
@@ -795,7 +805,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
     };
     auto stash = [&](int g, int h, const Regs &r) { // half h of granule g -> LDS buffer h; bytes past the row become zero
         unsigned char *buf = lds + h * (kRows * kMsLdsRow);
-        const bool ok = (int64_t)(it.c0 + g) * kMsGranuleBytes + h * kMsRowBytes + cb < row_bytes;
+        const bool ok = (int64_t)granule(g) * kMsGranuleBytes + h * kMsRowBytes + cb < row_bytes;
         const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int i = 0; i < kLoads; ++i)
@@ -908,7 +918,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void shrink_mfma_kernel(const MsIt
     uint16_t *vfrag = reinterpret_cast<uint16_t *>(args.v[cs] + args.vfrag_off);
     int8_t *vexp = reinterpret_cast<int8_t *>(args.v[cs] + args.vexp_off);
     float *partial = args.v[cs] + args.part_off + it.part_off;
-#define SLORA_MS(NBV, MBV) shrink_mfma_tile<DT, NBV, MBV>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, vexp, partial, lds)
+#define SLORA_MS(NBV, MBV) shrink_mfma_tile<DT, NBV, MBV>(it, pa, x, pool, tok_idx, H, v_stride, vfrag, vexp, partial, lds, args.n)
     if (it.ntok <= 64) {
         if (it.nj <= 32) SLORA_MS(1, 2);
         else if (it.nj <= 64) SLORA_MS(2, 2);

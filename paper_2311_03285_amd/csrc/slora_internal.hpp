@@ -149,7 +149,7 @@ struct slora_pool {
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
     int64_t fuse_decode = 1;                          // 0: never, 1: when the batch has enough small groups, 2: always
     int64_t shrink_pages = 4;                         // pages of A per vector-shrink item (its x rows are staged once for all of them)
-    int64_t mfma_split_bytes = 256 << 10;             // MFMA shrink: a tile's H range is cut into shares of about this many row bytes
+    int64_t mfma_split_bytes = 1 << 20;               // MFMA shrink: a tile's H range is cut into shares of about this many row bytes
     int64_t mfma_split_min_h = 1024;                  // ... but no share is shorter than this many elements of H
 
     // recycled buffer sets (plans, page writes) and the stream that carries work-list uploads

@@ -163,6 +163,7 @@ def test_scheduler_shares_of_H_and_one_launch_decode_groups():
         slora.adapter_load(p, a, r, np.arange(at, at + 8 * r))
         at += 8 * r
     slora.set_option(p, "mfma_min_tiles", 1)
+    slora.set_option(p, "mfma_split_bytes", 256 << 10)        # shares of about 256 KiB of rows
     ids = [0] * 300 + [1] * 130 + [2] * 20
     seg = [0, 300, 430, 450]
     plan = slora.batch_plan(p, ids, seg)
