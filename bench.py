@@ -23,16 +23,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
-# scaled by what the counter reads for the library's plain page-copy kernel of known size
-# (profiles/cfg4_decode_hbm_traffic.md); only for the default command lines of these workloads
-# with fp32 y.
-MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 324734 * 1024,
-                                                                        "shrink_vec": 304298 * 1024,
+# HBM bytes per launch of a stage from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
+# the counter reads for the library's plain page-copy kernel of known size: FETCH_SIZE / factor +
+# WRITE_SIZE, summed over the kernels of the stage (the MFMA shrink counts with its join kernel).
+# From the committed counter summaries named in "source"; only for the default command lines of
+# these workloads with fp32 y.  On cfg5 the figures are those of the two-stage kernels the
+# per-stage timing loop launches (a whole apply runs the decode groups in one kernel instead).
+MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 332626814,
+                                                                        "shrink_vec": 311911222,
                                                                         "source": "profiles/cfg4_decode_hbm_traffic.md"},
-                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 666887 * 1024,
-                                                            "shrink_mfma": 293524 * 1024,
-                                                            "source": "profiles/cfg3_prefill_hbm_traffic.md"}}
+                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 690861928,
+                                                            "shrink_mfma": 214488507 + 7845935,
+                                                            "source": "profiles/cfg3_prefill_hbm_traffic.md"},
+                    ("cfg5-mixed", "power", "fused", 8): {"expand_vec+mfma": 2791931804 + 1373454758,
+                                                          "shrink_vec+mfma": 799724205 + 36356229 + 1299029047,
+                                                          "source": "profiles/cfg5_mixed_hbm_traffic.md"}}
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
 
 
