@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 332626814,
                                                                         "shrink_vec": 311911222,
                                                                         "source": "profiles/cfg4_decode_hbm_traffic.md"},
-                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 690861928,
-                                                            "shrink_mfma": 214488507 + 7845935,
+                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 690829086,
+                                                            "shrink_mfma": 214447084 + 7845357,
                                                             "source": "profiles/cfg3_prefill_hbm_traffic.md"},
                     ("cfg5-mixed", "power", "fused", 8): {"expand_vec+mfma": 2791931804 + 1373454758,
                                                           "shrink_vec+mfma": 799724205 + 36356229 + 1299029047,

@@ -24,6 +24,14 @@
  *   - Storage type of pool pages and of x is IEEE binary16 or bfloat16; y and the
  *     intermediate v = x*A are fp32; all accumulation is fp32.  No alpha/r scaling is applied
  *     (Eq. 2 has none): fold any scale into B before upload.
+ *     Range of v: adapter groups that run on the matrix cores (prefill segments, Sec. 5.3) hand
+ *     v to the second product as 16-bit pieces whose sum is the fp32 value.  For bfloat16 pools
+ *     that holds over the whole fp32 range.  For binary16 pools every token row of v is scaled
+ *     by a power of two first (exponent clamped to [-24, 40]): rows whose largest |v| (per 128
+ *     ranks) lies in [2^-42, 2^35) are carried to 22 bits relative to that largest value, like
+ *     the fp32 sums they come from; smaller rows keep an absolute error of 2^-64; from 2^40 on
+ *     the pieces overflow and y becomes inf/NaN where the vector kernels and a plain fp32
+ *     evaluation would still be finite.
  *   - Page j of an adapter's A list holds column j of A (an H-vector), page j of its B list
  *     holds row j of B.  All projections map H -> H.
  *   - The pool memory is borrowed from the caller and never allocated, freed or cleared here.

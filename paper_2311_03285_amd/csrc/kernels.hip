@@ -611,7 +611,7 @@ __device__ __forceinline__ void split_pieces(const float (&f)[8], u32x4 (&piece)
 // The finished tile goes to the expand as MFMA operand fragments (see VPieces).  For binary16
 // pools every token row is first scaled by a power of two, 2^e, that puts its largest |v| into
 // [2^10, 2^11): the hi piece then holds 11 bits and the lo piece 11 more whatever the magnitude
-// of v, and v up to 2^35 cannot overflow the 16-bit format.  e (clamped to [-24, 40]) is left
+// of v (row maxima in [2^-42, 2^35); the pieces overflow from 2^40 on).  e (clamped to [-24, 40]) is left
 // beside the fragments; the expand scales its accumulators by 2^e and back.
 // Token rows beyond the item and ranks beyond the adapter's are read from a valid row instead;
 // their results are not stored, or stored as zero (ranks up to the next multiple of 32, so the
