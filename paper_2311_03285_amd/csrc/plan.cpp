@@ -175,8 +175,9 @@ int32_t slora::build_plan(slora_pool *pool, slora_plan *plan, const int32_t *ids
         // group streams the whole adapter.  That pays when the batch has enough groups to fill
         // the GPU about three times over with whole-group workgroups AND the groups are large
         // (a workgroup's waits for its work item, page lists and first pages are then short beside
-        // its streaming): measured per step, 2.39 -> 2.27 ms on the mixed configuration (H = 8192,
-        // 2.3 MB of pages per group), 111 -> 113 us on the large-pool decode one (0.6 MB per group).
+        // its streaming): measured per step inside one process, 2.41 -> 2.38 ms on the mixed
+        // configuration (H = 8192, 2.3 MB of pages per group); on the large-pool decode one (0.6 MB
+        // per group) 109.0 -> 112.3 us in one process and 111.7 -> 110.8 us in the next.
         // x rows are staged in LDS (64 KiB: H <= 8192).
         int64_t n_small = 0, small_bytes = 0;
         for (int32_t gi : order) {
