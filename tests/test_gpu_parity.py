@@ -380,6 +380,62 @@ def test_random_shapes_against_the_oracle(seed):
         assert np.all(np.abs(dec(got16) - ref) <= tol)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_options_and_entry_points_against_the_oracle(seed):
+    """Seeded random batches as above, with the tuning options drawn at random too (routing
+    thresholds, share size and shortest share of the MFMA shrink, the one-launch decode rule,
+    pages per vector-shrink item, tile grouping), one to four slots in one call in a random
+    order, through a randomly chosen entry point: the multi-slot apply, the apply that
+    allocates nothing, shrink and expand as two calls, or the one-shot call per slot.  None of
+    this may change the result beyond rounding: every slot against the oracle at the regression
+    bar, rows without an adapter bit for bit."""
+    g = np.random.default_rng(77000 + seed)
+    H = int(g.choice([64, 72, 200, 512, 1000, 1536, 2048, 4104]))
+    dtype = int(g.integers(0, 2))
+    n_ad = int(g.integers(1, 10))
+    ranks = tuple(int(r) for r in g.choice([0, 1, 2, 7, 8, 16, 31, 32, 33, 64, 65, 96, 128, 129, 160], size=n_ad))
+    n_seg = int(g.integers(1, 24))
+    lens = [int(v) for v in g.choice([1, 1, 1, 1, 2, 3, 4, 5, 17, 32, 33, 64, 70, 127, 128, 129, 150], size=n_seg)]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ids = np.repeat(g.integers(-1, n_ad, size=n_seg), lens).astype(np.int32)
+    n_slots = int(g.integers(1, 5))
+    decode = bool(g.integers(0, 4) == 0)
+    w = synth.make_workload("random-options", 77000 + seed, H, dtype, int(n_slots * 4 * sum(ranks) + 64), n_slots, ranks, ids,
+                            None if decode else seg)
+    opts = {"mfma_min_tokens": int(g.choice([1, 4, 16, VEC_ONLY])), "mfma_min_tiles": int(g.choice([1, 1, 4, 32])),
+            "mfma_split_bytes": int(g.choice([1 << 16, 1 << 18, 1 << 20, 1 << 30])),
+            "mfma_split_min_h": int(g.choice([128, 256, 1024])), "fuse_decode": int(g.integers(0, 3)),
+            "shrink_pages": int(g.integers(1, 9)), "xcd_group": int(g.integers(0, 4))}
+    entry = ["multi", "static", "two_calls", "one_shot"][int(g.integers(0, 4))]
+    what = f"seed {seed} H={H} ranks={ranks} lens={lens} decode={decode} {opts} {entry}"
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        for k, v in opts.items():
+            slora.set_option(dw.pool, k, v)
+        st = torch.cuda.Stream()
+        plan = dw.plan()
+        slots = [int(s) for s in g.permutation(n_slots)]
+        xs = [dw.x_dev(s) for s in slots]
+        ys = [dw.y_dev(s) for s in slots]
+        xp, yp = [x.data_ptr() for x in xs], [y.data_ptr() for y in ys]
+        if entry == "multi":
+            slora.lora_apply_multi(plan, slots, xp, yp, st)
+        elif entry == "static":
+            slora.lora_apply_multi_static(plan, slots, xp, yp, st)
+        elif entry == "two_calls":
+            slora.lora_shrink(plan, slots, xp, st)
+            slora.lora_expand(plan, slots, yp, st)
+        else:
+            for s, x, y in zip(slots, xp, yp):
+                slora.lora_shrink_expand(dw.pool, s, x, w.ids, w.seg_offsets, y, st)
+        torch.cuda.synchronize()
+        untouched = (w.ids < 0) | (w.ranks[np.maximum(w.ids, 0)] == 0)
+        for s, y in zip(slots, ys):
+            got = y.cpu().numpy()
+            assert np.array_equal(got[untouched], w.y_in(s)[untouched]), what
+            if (~untouched).any():
+                assert_close(got, oracle_slot(w, s), f"slot {s} {what}", rel_bar=5e-6)
+
+
 # ------------------------------------------------------------------ decode groups in one launch
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 @pytest.mark.parametrize("H", [64, 1000, 5120, 6656, 8192])
