@@ -119,7 +119,20 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
             for s in slots:
                 apply_one(p, s, x_of(b, s), ys[b][s].data_ptr(), stream)
 
-    # ---- timed region: K steps, inputs resident -------------------------------------------
+    # ---- set-up: every rotating batch is applied once, so that each plan owns its v scratch
+    # (the first apply of a plan allocates it) whatever the number of warm-up steps -----------
+    # and the device is kept busy for a while: after the host-side set-up it has been idle for
+    # seconds, and the first milliseconds of work after that run below the steady-state rate.
+    spin = []
+    t_spin = time.perf_counter()
+    while len(spin) < 2 or (time.perf_counter() - t_spin < args.spin_ms * 1e-3 and len(spin) < 10000):
+        ta = time.perf_counter()
+        for b in range(R):
+            step(b)
+        torch.cuda.synchronize()
+        spin.append((time.perf_counter() - ta) * 1e3 / R)
+    log(f"[bench] set-up rotations, ms per step: first {spin[0]:.4f}, second {spin[1]:.4f}, last {spin[-1]:.4f} ({len(spin)} rotations)")
+    # ---- timed region: W warm-up steps, then K steps, inputs resident -----------------------
     for i in range(args.warmup):
         step(i % R)
     torch.cuda.synchronize()
@@ -219,19 +232,29 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         f1.record(stream)
     torch.cuda.synchronize()
     launch_floor_us = f0.elapsed_time(f1) * 1e3 / 200
-    tok_per_step = float(np.mean([w.T for w in wls]))
-    bytes_step = float(np.mean([w.algorithmic_bytes() for w in wls])) * n_slots
+    # The K timed steps visit batch i % R: when K is no multiple of R the batches (which differ in
+    # size) are not visited equally often, so tokens, bytes and flops per step are averaged with
+    # the weights of the steps that were timed.
+    mix = np.bincount([i % R for i in range(args.steps)], minlength=R) / float(args.steps)
+    avg = lambda f, wts=mix: float(np.dot(wts, [float(f(w)) for w in wls]))
+
+    def step_bytes(wts):
+        b = avg(lambda w: w.algorithmic_bytes(), wts) * n_slots
+        if args.y16:        # y read + written as 2-byte elements instead of 4-byte ones
+            b -= 2 * avg(lambda w: np.count_nonzero(w.ids >= 0) * w.H, wts) * 2 * n_slots
+        if args.shared_x:
+            # x of a layer's q, k, v counted once: two of every four slots' x reads drop out
+            b -= avg(lambda w: np.count_nonzero(w.ids >= 0) * w.H * 2, wts) * sum(1 for s in range(n_slots) if s % 4 in (1, 2))
+        return b
+
+    tok_per_step = avg(lambda w: w.T)
+    bytes_step = step_bytes(mix)
+    bytes_step_even = step_bytes(np.full(R, 1.0 / R))      # for the per-step brackets, which cycle evenly
     t_act_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H for w in wls]))
-    if args.y16:        # y read + written as 2-byte elements instead of 4-byte ones
-        bytes_step -= 2 * t_act_b * 2 * n_slots
-    if args.shared_x:
-        # x of a layer's q, k, v counted once: two of every four slots' x reads drop out
-        x_b = float(np.mean([np.count_nonzero(w.ids >= 0) * w.H * 2 for w in wls]))
-        bytes_step -= x_b * sum(1 for s in range(n_slots) if s % 4 in (1, 2))
-    flops_step = float(np.mean([w.flops() for w in wls])) * n_slots
+    flops_step = avg(lambda w: w.flops()) * n_slots
     # the same traffic if every token fetched its adapter's pages for itself (no sharing)
-    naive_step = float(np.mean([int(2 * w.ranks[w.ids[w.ids >= 0]].astype(np.int64).sum()) * w.H * 2 +
-                                np.count_nonzero(w.ids >= 0) * w.H * (2 + 8) for w in wls])) * n_slots
+    naive_step = avg(lambda w: int(2 * w.ranks[w.ids[w.ids >= 0]].astype(np.int64).sum()) * w.H * 2 +
+                     np.count_nonzero(w.ids >= 0) * w.H * (2 + 8)) * n_slots
     value = tok_per_step * args.steps / wall
 
     # ---- per-kernel durations: HIP events on the launch stream around runs of one stage ----------
@@ -280,9 +303,8 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
         "bound": "hbm", "kernel": f"{dom}_{kinds}", "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
         "traffic": traffic.get(f"{dom}_{kinds}"),
-        "traffic_source": (None if not traffic else
-                           f"{traffic['source']} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command "
-                           "line, taken earlier: counters cannot be read inside a timed run)"),
+        # counters cannot be read inside a timed run: the figure comes from the committed summary
+        "traffic_source": (None if not traffic else f"{traffic['source']} (earlier rocprofv3 --pmc runs of this command)"),
         "algorithmic_bytes_per_launch": int((ex_b if dom == "expand" else sh_b) * min(n_slots, slora.MAX_MULTI)),
         "avg_launch_us": round((ex_t if dom == "expand" else sh_t) * 1e6, 2),
         "other_kernel": {"kernel": f"{'shrink' if dom == 'expand' else 'expand'}_{kinds}",
@@ -320,7 +342,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
             mx = max(mx, float(np.abs(got - ref).max()))
         del yg
     parity = {"slots_checked": n_slots, "tokens_checked_per_slot": n_samp, "of_tokens": int(act.size),
-              "rel_l2": rel, "max_abs": mx, "bars": {"rel_l2": 1e-3, "max_abs": 1e-2}}
+              "rel_l2": float(f"{rel:.3e}"), "max_abs": float(f"{mx:.3e}"), "bars": {"rel_l2": 1e-3, "max_abs": 1e-2}}
     if not (np.isfinite(rel) and rel <= 1e-3 and mx <= 1e-2):
         raise RuntimeError(f"GPU result disagrees with the oracle (rel-L2 {rel:.3e}, max-abs {mx:.3e})")
 
@@ -539,7 +561,7 @@ def measure(args, workload: int, no_cpu: bool) -> dict:
                    "distinct_adapters_per_batch": float(np.mean([len(w.used_adapters()) for w in wls]))},
         "hbm_gbps": round(bytes_step / (wall / args.steps) / 1e9, 1),
         "hbm_frac": round(bytes_step / (wall / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
-        "hbm_frac_median_step": round(bytes_step / (cold_med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "hbm_frac_median_step": round(bytes_step_even / (cold_med * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "mfma_util": round(flops_step / (wall / args.steps) / 1e12 / MFMA_PEAK_TFLOPS, 5),
         # the most the matrix cores can be busy while HBM keeps up: arithmetic intensity x 8 TB/s
         "mfma_util_cap": round(flops_step / bytes_step * HBM_PEAK_GBS * 1e9 / (MFMA_PEAK_TFLOPS * 1e12), 5),
@@ -589,6 +611,8 @@ def main() -> int:
                     help="q, k, v of a layer read the same x buffer (as in a model); its bytes are counted once")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--graph", action="store_true", help="replay the steps as one HIP graph per rotation")
+    ap.add_argument("--spin-ms", type=float, default=50.0,
+                    help="untimed set-up: rotations over the batches until this much time has passed (at least two)")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option key=value (repeatable)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="core-seconds of oracle work to time")
     ap.add_argument("--parity-tokens", type=int, default=32,
@@ -611,7 +635,14 @@ def main() -> int:
             out["also"] = []
             for n in (int(v) for v in args.also.split(",")):
                 o = measure(args, n, True)
-                out["also"].append({k: o[k] for k in keep if k in o})
+                e = {k: o[k] for k in keep if k in o}
+                # the nested summaries stay short: the full objects come from `--workload n`
+                e["config"] = {k: o["config"][k] for k in ("workload", "H", "storage", "tokens_per_step", "slots")}
+                e["roofline"] = {k: o["roofline"][k] for k in ("kernel", "achieved", "frac", "traffic", "traffic_source",
+                                                              "algorithmic_bytes_per_launch", "avg_launch_us",
+                                                              "other_kernel", "slots_per_launch")}
+                e["parity"] = {k: o["parity"][k] for k in ("slots_checked", "tokens_checked_per_slot", "rel_l2", "max_abs")}
+                out["also"].append(e)
     except RuntimeError as e:
         print(f"bench.py: {e}", file=sys.stderr)
         return 1
