@@ -145,7 +145,7 @@ struct slora_pool {
     int64_t live_plans = 0;
     int64_t mfma_min_tokens = 16;
     int64_t mfma_min_tiles = 32;
-    int64_t xcd_group = 0;                            // bit 0: MFMA shrink list grouped per XCD, bit 1: expand list
+    int64_t xcd_group = 0;                            // bit 1: MFMA expand list grouped per XCD (bit 0, once the same for the shrink list, is ignored)
     int64_t upload_groups = 32;                       // workgroups of an adapter upload from host memory
     int64_t fuse_decode = 1;                          // 0: never, 1: when the batch has enough small groups, 2: always
     int64_t shrink_pages = 4;                         // pages of A per vector-shrink item (its x rows are staged once for all of them)
