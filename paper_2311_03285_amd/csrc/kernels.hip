@@ -803,19 +803,33 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
             }
         }
     };
+    const int last_gran = (int)((row_bytes - 1) / kMsGranuleBytes);
+    const bool ragged = row_bytes % kMsGranuleBytes != 0; // only then can a granule reach past the row
     auto stash = [&](int g, int h, const Regs &r) { // half h of granule g -> LDS buffer h; bytes past the row become zero
         unsigned char *buf = lds + h * (kRows * kMsLdsRow);
-        const bool ok = (int64_t)granule(g) * kMsGranuleBytes + h * kMsRowBytes + cb < row_bytes;
-        const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+        const int gg = granule(g);
+        if (ragged && gg == last_gran) { // uniform over the workgroup
+            const bool ok = (int64_t)gg * kMsGranuleBytes + h * kMsRowBytes + cb < row_bytes;
+            const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i)
-            *reinterpret_cast<u32x4 *>(buf + (r8 + kMsRowsPerPass * i) * kMsLdsRow + cb) = ok ? r.w[h][i] : zero;
+            for (int i = 0; i < kLoads; ++i)
+                *reinterpret_cast<u32x4 *>(buf + (r8 + kMsRowsPerPass * i) * kMsLdsRow + cb) = ok ? r.w[h][i] : zero;
+        } else {
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i)
+                *reinterpret_cast<u32x4 *>(buf + (r8 + kMsRowsPerPass * i) * kMsLdsRow + cb) = r.w[h][i];
+        }
     };
-    f32x16 acc[NB];
+    // A single rank block would make every MFMA wait for the one before it (they share the
+    // accumulator): such tiles keep two accumulators, for alternate k-steps, added at the end.
+    constexpr int KA = NB == 1 ? 2 : 1;
+    f32x16 acc[NB][KA];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+        for (int a = 0; a < KA; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[nb][a][e] = 0.f;
     auto compute = [&](int h) { // the four k-steps of the chunk in LDS buffer h, for this wavefront's token block
         if (wave >= MB) return;
         const unsigned char *buf = lds + h * (kRows * kMsLdsRow);
@@ -828,7 +842,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
             for (int nb = 0; nb < NB; ++nb)
                 pb[nb] = *reinterpret_cast<const u32x4 *>(buf + (32 * MB + nb * 32 + row) * kMsLdsRow + kb);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma32<DT>(xa, pb[nb], acc[nb]);
+            for (int nb = 0; nb < NB; ++nb) acc[nb][k % KA] = mfma32<DT>(xa, pb[nb], acc[nb][k % KA]);
         }
     };
 
@@ -871,7 +885,11 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
     for (int nb = 0; nb < NB; ++nb) {
         if (live && nb < nb_act) {
 #pragma unroll
-            for (int vv = 0; vv < 16; ++vv) stage[mfma_row(vv, lane) * kEpiStride + row] = acc[nb][vv];
+            for (int vv = 0; vv < 16; ++vv) {
+                float sum = acc[nb][0][vv];
+                if constexpr (KA == 2) sum += acc[nb][1][vv];
+                stage[mfma_row(vv, lane) * kEpiStride + row] = sum;
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
