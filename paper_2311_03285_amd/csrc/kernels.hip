@@ -786,7 +786,7 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
         const int k = min(g, n_gran - 1) + g_first;
         return it.c0 + (k < n_gran ? k : k - n_gran);
     };
-    auto load = [&](int g, Regs &r) { // g-th granule of the share (clamped to the last one), bytes clamped into the row
+    auto load = [&](int g, Regs &r) { // g-th granule of the share, bytes clamped into the row
         const int gg = granule(g);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -847,28 +847,42 @@ __device__ __forceinline__ void shrink_mfma_tile(const MsItem &it, const int32_t
     };
 
     // register ring: granule g is copied to LDS, half by half, while granule g+1 is still in
-    // flight and granule g+kRing is requested (granules past the end re-read the last one and
-    // are dropped).  The two halves use the two LDS buffers, one barrier each.
+    // flight and granule g+2 is requested.  The two halves use the two LDS buffers, one barrier
+    // each.  The last granules, which have nothing left to request, are peeled off the loop: its
+    // body then has no condition in it, and nothing is fetched that is not used.
+    static_assert(kRing == 2, "the peeled loop below is written for a ring of two");
+    auto step = [&](int g, Regs &r, bool more) { // `more`: granule g + 2 exists and is requested into r
+        stash(g, 0, r);
+        __syncthreads();
+        compute(0);
+        stash(g, 1, r);
+        if (more) load(g + 2, r);
+        __syncthreads();
+        compute(1);
+    };
     Regs ring[kRing];
-#pragma unroll
-    for (int d = 0; d < kRing; ++d) {
-        load(d, ring[d]);
-        // keep the granules' loads in issue order: the wait before a granule is copied to LDS
-        // then counts only the loads of the younger one as outstanding
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    const int n_rounds = (n_gran + kRing - 1) / kRing;
-    for (int rd = 0; rd < n_rounds; ++rd) {
-#pragma unroll
-        for (int d = 0; d < kRing; ++d) {
-            const int g = rd * kRing + d;
-            stash(g, 0, ring[d]);
-            __syncthreads();
-            if (g < n_gran) compute(0);
-            stash(g, 1, ring[d]);
-            load(g + kRing, ring[d]);
-            __syncthreads();
-            if (g < n_gran) compute(1);
+    load(0, ring[0]);
+    // keep the granules' loads in issue order: the wait before a granule is copied to LDS then
+    // counts only the loads of the younger one as outstanding
+    __builtin_amdgcn_sched_barrier(0);
+    load(n_gran > 1 ? 1 : 0, ring[1]); // a share of one granule fetches it twice
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (kLoads <= 6) {
+        int g = 0;
+        for (; g + 3 < n_gran; g += 2) {
+            step(g, ring[0], true);
+            step(g + 1, ring[1], true);
+        }
+        // one to three granules are left; only the first of three still has one to request
+        step(g, ring[0], g + 2 < n_gran);
+        if (g + 1 < n_gran) step(g + 1, ring[1], false);
+        if (g + 2 < n_gran) step(g + 2, ring[0], false);
+    } else {
+        // the widest tiles have no register to spare for the peeled copies: their loop keeps
+        // requesting (the last granule again, dropped) to its end
+        for (int g = 0; g < n_gran; g += 2) {
+            step(g, ring[0], true);
+            if (g + 1 < n_gran) step(g + 1, ring[1], true);
         }
     }
     __syncthreads(); // the chunk buffers are free: each wavefront now stages its tiles in its own part
