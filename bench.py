@@ -29,14 +29,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # From the committed counter summaries named in "source"; only for the default command lines of
 # these workloads with fp32 y.  On cfg5 the figures are those of the two-stage kernels the
 # per-stage timing loop launches (a whole apply runs the decode groups in one kernel instead).
-MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 332874299,
-                                                                        "shrink_vec": 312123923,
+MEASURED_TRAFFIC = {("cfg4-large-pool-decode", "power", "fused", 8): {"expand_vec": 332880461,
+                                                                        "shrink_vec": 312123908,
                                                                         "source": "profiles/cfg4_decode_hbm_traffic.md"},
-                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 690128908,
-                                                            "shrink_mfma": 213402226 + 7896363,
+                    ("cfg3-prefill", "power", "fused", 8): {"expand_mfma": 690047714,
+                                                            "shrink_mfma": 209097830 + 7899366,
                                                             "source": "profiles/cfg3_prefill_hbm_traffic.md"},
-                    ("cfg5-mixed", "power", "fused", 8): {"expand_vec+mfma": 2805117189 + 1373454991,
-                                                          "shrink_vec+mfma": 802617677 + 36335121 + 1299029077,
+                    ("cfg5-mixed", "power", "fused", 8): {"expand_vec+mfma": 2804682598 + 1373456197,
+                                                          "shrink_vec+mfma": 768431054 + 36335013 + 1299029045,
                                                           "source": "profiles/cfg5_mixed_hbm_traffic.md"}}
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA, published
 
