@@ -350,3 +350,55 @@ def test_config3_every_slot():
 
 def test_config5_every_slot():
     _all_slots(5)
+
+
+# ------------------------------------------------------------------ HIP graph capture of every kernel
+@pytest.mark.parametrize("entry", ["multi", "static"])
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_mixed_batch_captured_in_a_hip_graph(dtype, entry):
+    """A mixed batch whose apply launches every kernel the library has - the MFMA shrink with
+    shared-out tiles, the join of their partial sums, the one-launch decode kernel, the
+    two-stage vector kernels (a nine-token group), the MFMA expand - captured in a HIP graph
+    through the allocating entry point (scratch sized by an eager call first) and through the
+    one that allocates nothing.  Every replay, with the program's own eager work in between,
+    must reproduce the eager result bit for bit; the eager result meets the oracle."""
+    lens = (1, 1, 2, 4, 9, 1, 3, 40, 130, 1, 1, 100)
+    ranks = (8, 16, 64, 128, 33, 160, 7, 32, 1, 5, 17, 96)
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_ad = np.random.default_rng(2600 + dtype).permutation(len(ranks))
+    seg_ad[5] = -1                                       # one decode token without adapter
+    ids = np.repeat(seg_ad, lens).astype(np.int32)
+    w = synth.make_workload("graph-mixed", 2600 + dtype, 1024, dtype, 3000, 2, ranks, ids, seg)
+    with DeviceWorkload(w, real_adapters="all", max_rank=160) as dw:
+        route(dw.pool, 16)
+        slora.set_option(dw.pool, "mfma_split_bytes", 1 << 16)
+        slora.set_option(dw.pool, "mfma_split_min_h", 128)
+        slora.set_option(dw.pool, "fuse_decode", 2)
+        plan = dw.plan()
+        info = slora.plan_info(plan)
+        assert info["split_tiles"] > 0 and info["groups_fused"] > 0 and info["groups_mfma"] > 0
+        assert info["groups_fused"] < info["groups_vec"]          # the nine-token group stays on two kernels
+        apply = slora.lora_apply_multi if entry == "multi" else slora.lora_apply_multi_static
+        x = [dw.x_dev(0), dw.x_dev(1)]
+        y0 = [dw.y_dev(0), dw.y_dev(1)]
+        y = [t.clone() for t in y0]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            apply(plan, [0, 1], [t.data_ptr() for t in x], [t.data_ptr() for t in y], torch.cuda.current_stream())
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        eager = [t.cpu().numpy() for t in y]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            apply(plan, [0, 1], [t.data_ptr() for t in x], [t.data_ptr() for t in y], torch.cuda.current_stream())
+        for rep in range(4):
+            for k in range(2):
+                y[k].copy_(y0[k])               # eager work between the replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for k in range(2):
+                assert np.array_equal(y[k].cpu().numpy(), eager[k]), (rep, k)
+        for k in range(2):
+            assert_close(eager[k], oracle_slot(w, k), f"graph slot {k}", rel_bar=5e-6)
